@@ -1,0 +1,160 @@
+/*
+ * bass.h -- C ABI of the BASS verification step for AMD MI355X (gfx950).
+ *
+ * BASS = batched speculative sampling: B sequences are verified at once by the main
+ * model; every sequence brings its own number of draft query tokens and its own,
+ * differently long KV cache (ragged K, V, P tensors), then per-sequence
+ * speculative-sampling acceptance decides how many drafts are kept.
+ *
+ * Conventions for every call
+ *   - Pointers are DEVICE pointers unless a parameter says "host".  They are borrowed:
+ *     the library never frees or retains them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; they never synchronise and never allocate.
+ *   - Return value: BASS_OK (0) or a negative error found on the host BEFORE anything is
+ *     enqueued (see the enum).  Errors that depend on device data (a length out of range,
+ *     a token id >= V) cannot be seen by the host: the kernels clamp to a safe range and
+ *     OR a BASS_STATUS_* bit into `*dev_status` (int32 on the device, optional, may be
+ *     NULL; the caller zeroes it).
+ *   - One GPU; calls on the same stream are ordered; calls on different streams must not
+ *     share a workspace.
+ */
+#ifndef BASS_H
+#define BASS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  BASS_OK = 0,
+  BASS_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, Hq % Hkv != 0 ...      */
+  BASS_ERR_UNSUPPORTED = -2,        /* head size / dtype / row count outside what is compiled  */
+  BASS_ERR_WORKSPACE_TOO_SMALL = -3,
+  BASS_ERR_HIP = -4                 /* a launch failed; hipGetLastError() still holds the code */
+};
+
+enum {
+  BASS_STATUS_LEN_CLAMPED = 1,      /* a ctx_len / draft_len / n_new / n_draft was out of range */
+  BASS_STATUS_TOKEN_CLAMPED = 2,    /* a draft token id was outside [0, V)                      */
+  BASS_STATUS_ZERO_MASS = 4         /* a probability row had no mass to sample from             */
+};
+
+enum { BASS_DTYPE_BF16 = 0, BASS_DTYPE_FP32 = 1 };
+
+/* Shape of one attention layer's verification call. */
+typedef struct bass_attn_desc {
+  int32_t B;      /* sequences in the batch                                                     */
+  int32_t kmax;   /* query-token slots per sequence (tensors are padded to kmax)                */
+  int32_t Hq;     /* query heads                                                                */
+  int32_t Hkv;    /* key/value heads, Hq % Hkv == 0 (query head h uses kv head h / (Hq/Hkv))     */
+  int32_t D;      /* head size: 64 or 128 for bf16; a multiple of 4 up to 256 for fp32           */
+  int32_t Lcap;   /* cache capacity in tokens per sequence                                      */
+  int32_t dtype;  /* BASS_DTYPE_*: element type of Q, K, V, K_new, V_new; O is always fp32       */
+  float scale;    /* the 1/c of P = softmax(Q^T K / c) (Section 3.2); callers pass 1/sqrt(D)     */
+} bass_attn_desc;
+
+int bass_version(void);
+const char* bass_status_string(int code); /* static string, host */
+
+/* Bytes of ONE cache (K or V) for this shape.  The cache layout is owned by the library
+ * (bf16 caches are stored in matrix-core fragment order); a cache is written only through
+ * bass_kv_append and read back only through bass_kv_gather.  Returns 0 for a bad shape. */
+size_t bass_kv_cache_bytes(const bass_attn_desc* desc);
+
+/* Scratch bytes bass_verify_attention needs for this shape (split-context partial
+ * results).  Returns 0 for a bad shape. */
+size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* desc);
+
+/*
+ * Append this step's key/value rows to the per-sequence caches (Section 2.1: keys and
+ * values of processed tokens are cached; Section 3.2: every sequence proceeds at its own
+ * pace, so each has its own write offset; rows of rejected drafts are simply overwritten
+ * by the next step).
+ *   K_new, V_new [B, kmax, Hkv, D]  rows of the new tokens (desc->dtype)
+ *   ctx_len      [B] int32          write offset (tokens already valid) of each sequence
+ *   n_new        [B] int32          rows to write, 0..kmax
+ * Row i < n_new[b] of sequence b becomes cache token ctx_len[b] + i.  Rows that would fall
+ * outside [0, Lcap) are dropped and BASS_STATUS_LEN_CLAMPED is raised.  Also used to fill a
+ * cache with a whole prompt (kmax = prompt length, ctx_len = 0).
+ */
+int bass_kv_append(const bass_attn_desc* desc, void* Kcache, void* Vcache, const void* K_new,
+                   const void* V_new, const int32_t* ctx_len, const int32_t* n_new,
+                   int32_t* dev_status, void* stream);
+
+/*
+ * Read cache rows back in token-major order (inverse of bass_kv_append; for tests and for
+ * moving a sequence): K_out, V_out [B, kmax, Hkv, D] receive tokens
+ * start[b] .. start[b]+n[b]-1 of sequence b; other rows are left untouched.
+ */
+int bass_kv_gather(const bass_attn_desc* desc, const void* Kcache, const void* Vcache, void* K_out,
+                   void* V_out, const int32_t* start, const int32_t* n, int32_t* dev_status,
+                   void* stream);
+
+/*
+ * Ragged verify attention (Section 3.2, attention flow: scores of the current tokens'
+ * queries against the keys of all tokens processed so far, P = softmax(Q^T K / c), then
+ * P times V; Section 2.2: the draft tokens are processed as incremental context encoding).
+ *   Q         [B, kmax, Hq, D]   queries of the current tokens (desc->dtype)
+ *   ctx_len   [B] int32          tokens cached BEFORE this step
+ *   draft_len [B] int32          query tokens of this step, 0..kmax (0 = inactive sequence)
+ *   O         [B, kmax, Hq, D]   fp32 output
+ *   lse       [B, kmax, Hq]      fp32 natural-log softmax denominator (max included);
+ *                                optional, may be NULL
+ * Query i of sequence b attends to cache tokens j <= ctx_len[b] + i: all of the sequence's
+ * own cache and, causally, the step's own tokens, whose K/V must already have been appended
+ * at [ctx_len[b], ctx_len[b] + draft_len[b]).  Every other position -- another sequence's
+ * tokens, padding, stale rows beyond the valid range -- has probability exactly zero, as
+ * padded positions have in BASS-PAD; no work is spent on them, as in BASS-SPLIT.  Rows
+ * i >= draft_len[b] of O and lse are written as 0.  ctx_len[b] = 0 is legal.
+ * Lengths outside the cache are clamped (BASS_STATUS_LEN_CLAMPED).
+ * bf16: kmax * (Hq/Hkv) <= 64.  `workspace` must hold at least
+ * bass_verify_attention_workspace_bytes(desc) bytes and be 16-byte aligned.
+ */
+int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void* Kcache,
+                          const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                          float* O, float* lse, void* workspace, size_t workspace_bytes,
+                          int32_t* dev_status, void* stream);
+
+/*
+ * Speculative-sampling acceptance for the batch (Section 2.2: the number of accepted
+ * drafts is decided from the main- and draft-model probabilities; on rejection a corrected
+ * token is sampled from the main model's outputs; the procedure is equivalent to sampling
+ * from the main model).
+ *   p          [B, kmax+1, V] fp32  main-model probabilities; row i judges draft i, row
+ *                                   n_draft[b] is the bonus row
+ *   q          [B, kmax,   V] fp32  draft-model probabilities
+ *   draft_tok  [B, kmax] int32      drafted token ids
+ *   n_draft    [B] int32            drafts of each sequence, 0..kmax
+ *   u          [B, kmax+1] fp32     uniforms in [0,1): u[b,i] judges draft i, u[b,kmax]
+ *                                   drives the corrected / bonus draw
+ *   n_accept   [B] int32 out        length of the accepted prefix
+ *   next_token [B] int32 out        corrected token (after a rejection) or bonus token
+ *   ctx_len    [B] int32 in/out     optional (may be NULL): += n_accept + 1
+ * Rule, per sequence: draft i with token x is accepted iff u_i * q_i(x) < p_i(x), evaluated
+ * exactly (fp64 product of fp32 values); the prefix stops at the first rejection.  The new
+ * token is drawn by inverse CDF from max(p_n - q_n, 0) (one fp32 subtraction per entry) after
+ * a rejection at position n, or from p_k after k acceptances, or from p_n if the residual has
+ * no mass.  Weights are floor(min(w,1) * 2^44) as integers, T = (floor(u * 2^32) * sum) >> 32,
+ * and the token is the first whose cumulative weight exceeds T, so the result does not
+ * depend on summation order.  V <= 2^19.
+ */
+int bass_spec_accept(int32_t B, int32_t kmax, int32_t V, const float* p, const float* q,
+                     const int32_t* draft_tok, const int32_t* n_draft, const float* u,
+                     int32_t* n_accept, int32_t* next_token, int32_t* ctx_len,
+                     int32_t* dev_status, void* stream);
+
+/*
+ * Tuning knob (host state, process wide): number of wavefronts the bf16/fp32 attention
+ * kernel spreads the flattened (sequence, kv-head, context-block) work over.  Values are
+ * clamped to [64, 8192]; 0 restores the default.  Returns the value in effect.
+ */
+int bass_set_attention_waves(int waves);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BASS_H */

@@ -1,0 +1,220 @@
+"""Python binding of libbass, the MI355X (gfx950) library for the BASS verification step.
+
+Argument marshalling only: every function here has the name and the argument order of
+the C entry point in include/bass.h and passes raw device pointers of torch tensors to it;
+all arithmetic runs in the HIP kernels.  torch is used for device memory and streams.
+There is no CPU fallback: without the built library (paper_2404_15778_amd/libbass.so,
+see build.py) importing works but every call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbass.so")
+
+OK = 0
+ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = -1, -2, -3, -4
+STATUS_LEN_CLAMPED, STATUS_TOKEN_CLAMPED, STATUS_ZERO_MASS = 1, 2, 4
+DTYPE_BF16, DTYPE_FP32 = 0, 1
+
+# every symbol include/bass.h declares
+EXPORTS = (
+    "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
+    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_spec_accept", "bass_set_attention_waves",
+)
+
+
+class AttnDesc(ctypes.Structure):
+    """Mirror of `bass_attn_desc`."""
+    _fields_ = [("B", ctypes.c_int32), ("kmax", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("Lcap", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+    def replace(self, **kw):
+        vals = {f: getattr(self, f) for f, _ in self._fields_}
+        vals.update(kw)
+        return AttnDesc(**vals)
+
+
+class BassError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what} failed: {code} ({bass_status_string(code)})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2404_15778_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp = ctypes.POINTER(AttnDesc)
+        L.bass_version.restype = ctypes.c_int
+        L.bass_status_string.restype = ctypes.c_char_p
+        L.bass_status_string.argtypes = [ctypes.c_int]
+        L.bass_kv_cache_bytes.restype = sz
+        L.bass_kv_cache_bytes.argtypes = [dp]
+        L.bass_verify_attention_workspace_bytes.restype = sz
+        L.bass_verify_attention_workspace_bytes.argtypes = [dp]
+        L.bass_kv_append.restype = ctypes.c_int
+        L.bass_kv_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_kv_gather.restype = ctypes.c_int
+        L.bass_kv_gather.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_verify_attention.restype = ctypes.c_int
+        L.bass_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+        L.bass_spec_accept.restype = ctypes.c_int
+        L.bass_spec_accept.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_set_attention_waves.restype = ctypes.c_int
+        L.bass_set_attention_waves.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def bass_version() -> int:
+    return int(lib().bass_version())
+
+
+def bass_status_string(code: int) -> str:
+    return lib().bass_status_string(int(code)).decode()
+
+
+def bass_set_attention_waves(waves: int) -> int:
+    return int(lib().bass_set_attention_waves(int(waves)))
+
+
+def make_desc(B, kmax, Hq, Hkv, D, Lcap, dtype, scale) -> AttnDesc:
+    code = {"bf16": DTYPE_BF16, "fp32": DTYPE_FP32}.get(dtype, dtype)
+    return AttnDesc(int(B), int(kmax), int(Hq), int(Hkv), int(D), int(Lcap), int(code), float(scale))
+
+
+def bass_kv_cache_bytes(desc: AttnDesc) -> int:
+    return int(lib().bass_kv_cache_bytes(ctypes.byref(desc)))
+
+
+def bass_verify_attention_workspace_bytes(desc: AttnDesc) -> int:
+    return int(lib().bass_verify_attention_workspace_bytes(ctypes.byref(desc)))
+
+
+# ---- marshalling helpers -------------------------------------------------------------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _elt_dtype(desc):
+    torch = _torch()
+    return torch.bfloat16 if desc.dtype == DTYPE_BF16 else torch.float32
+
+
+def _dev(t, name, dtype=None, shape=None, optional=False):
+    """Device pointer of a contiguous CUDA tensor after shape / dtype checks."""
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+    return ctypes.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _check(code, what):
+    if code != OK:
+        raise BassError(code, what)
+
+
+def _cache_ptr(t, desc, name):
+    if t is None or not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous GPU tensor")
+    if t.numel() * t.element_size() < bass_kv_cache_bytes(desc):
+        raise ValueError(f"{name} holds fewer than bass_kv_cache_bytes(desc) bytes")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+# ---- entry points (same names and argument order as include/bass.h) --------------------------
+
+def bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, n_new, dev_status=None, stream=None):
+    torch = _torch()
+    rows = (desc.B, desc.kmax, desc.Hkv, desc.D)
+    et = _elt_dtype(desc)
+    _check(lib().bass_kv_append(
+        ctypes.byref(desc), _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+        _dev(K_new, "K_new", et, rows), _dev(V_new, "V_new", et, rows),
+        _dev(ctx_len, "ctx_len", torch.int32, (desc.B,)), _dev(n_new, "n_new", torch.int32, (desc.B,)),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_kv_append")
+
+
+def bass_kv_gather(desc, Kcache, Vcache, K_out, V_out, start, n, dev_status=None, stream=None):
+    torch = _torch()
+    rows = (desc.B, desc.kmax, desc.Hkv, desc.D)
+    et = _elt_dtype(desc)
+    _check(lib().bass_kv_gather(
+        ctypes.byref(desc), _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+        _dev(K_out, "K_out", et, rows), _dev(V_out, "V_out", et, rows),
+        _dev(start, "start", torch.int32, (desc.B,)), _dev(n, "n", torch.int32, (desc.B,)),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_kv_gather")
+
+
+def bass_verify_attention(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace, dev_status=None,
+                          stream=None):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    if workspace is None or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _check(lib().bass_verify_attention(
+        ctypes.byref(desc), _dev(Q, "Q", _elt_dtype(desc), qshape),
+        _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+        _dev(ctx_len, "ctx_len", torch.int32, (desc.B,)), _dev(draft_len, "draft_len", torch.int32, (desc.B,)),
+        _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
+        ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_verify_attention")
+
+
+def bass_spec_accept(p, q, draft_tok, n_draft, u, n_accept, next_token, ctx_len=None, dev_status=None, stream=None):
+    torch = _torch()
+    if p is None or p.dim() != 3:
+        raise ValueError("p must be [B, kmax+1, V]")
+    B, k1, V = p.shape
+    kmax = k1 - 1
+    f32, i32 = torch.float32, torch.int32
+    _check(lib().bass_spec_accept(
+        B, kmax, V, _dev(p, "p", f32), _dev(q, "q", f32, (B, kmax, V), optional=(kmax == 0)),
+        _dev(draft_tok, "draft_tok", i32, (B, kmax), optional=(kmax == 0)), _dev(n_draft, "n_draft", i32, (B,)),
+        _dev(u, "u", f32, (B, kmax + 1)), _dev(n_accept, "n_accept", i32, (B,)),
+        _dev(next_token, "next_token", i32, (B,)), _dev(ctx_len, "ctx_len", i32, (B,), optional=True),
+        _dev(dev_status, "dev_status", i32, optional=True), _stream(stream)), "bass_spec_accept")
+
+
+# ---- allocation helpers (plumbing; no arithmetic) ----------------------------------------------
+
+def alloc_kv_cache(desc, device="cuda", fill_byte=None):
+    """One cache (K or V) as an opaque byte tensor; optionally filled with a byte pattern."""
+    torch = _torch()
+    t = torch.empty(bass_kv_cache_bytes(desc), dtype=torch.uint8, device=device)
+    if fill_byte is not None:
+        t.fill_(fill_byte)
+    return t
+
+
+def alloc_workspace(desc, device="cuda"):
+    torch = _torch()
+    return torch.empty(bass_verify_attention_workspace_bytes(desc), dtype=torch.uint8, device=device)

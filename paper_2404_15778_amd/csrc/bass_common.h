@@ -1,0 +1,75 @@
+// Internal helpers shared by the HIP translation units of libbass (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bass.h"
+
+namespace bass {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kBlockTokens = 32;   // tokens per cache block (one PV contraction step of the bf16 MFMA)
+constexpr int kMaxWaves = 8192;    // upper bound of the attention work spread (sizes the workspace)
+constexpr int kDefaultWaves = 2048;
+
+// ---------------------------------------------------------------------------------------
+// bf16 cache layout (library-owned).  A cache is [B][Hkv][nblk] blocks of 32 tokens; a block
+// holds 32*D bf16 stored in the order the matrix cores consume them, so that a wavefront
+// reads 1 KiB per load instruction (lane l reads bytes [16 l, 16 l + 16)) straight into an
+// MFMA operand.
+//   K block: [tile tt (2)][k-step t (D/32)][lane (64)][j (8)]
+//            lane = grp*16 + r holds token 16*tt + r, head elements d = 32*t + 8*grp + j
+//   V block: [d-tile mt (D/16)][lane (64)][j (8)]
+//            lane = grp*16 + dr holds head element d = 16*mt + dr of the eight tokens
+//            (j < 4: 4*grp + j ; j >= 4: 16 + 4*grp + (j-4))
+// The V token order is the order in which the score tile leaves the QK^T MFMA, which is why
+// the probabilities need no shuffle before the PV MFMA.
+// ---------------------------------------------------------------------------------------
+__host__ __device__ inline int num_blocks(int Lcap) { return (Lcap + kBlockTokens - 1) / kBlockTokens; }
+
+__host__ __device__ inline size_t k_elem_offset(int D, int tok_in_blk, int d) {
+  const int tt = tok_in_blk >> 4, r = tok_in_blk & 15;
+  const int t = d >> 5, grp = (d & 31) >> 3, j = d & 7;
+  return (size_t)(((tt * (D >> 5) + t) * 64 + grp * 16 + r) * 8 + j);
+}
+
+__host__ __device__ inline size_t v_elem_offset(int /*D*/, int tok_in_blk, int d) {
+  const int half = tok_in_blk >> 4, w = tok_in_blk & 15;
+  const int grp = w >> 2, j = half * 4 + (w & 3);
+  const int mt = d >> 4, dr = d & 15;
+  return (size_t)((mt * 64 + grp * 16 + dr) * 8 + j);
+}
+
+// Per-sequence lengths with the clamping the header promises.  L = cached tokens before the
+// step, nq = query tokens; on return 0 <= nq <= kmax, 0 <= L, L + nq <= Lcap.
+__device__ inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {
+  bool bad = false;
+  if (nq < 0) { nq = 0; bad = true; }
+  if (nq > kmax) { nq = kmax; bad = true; }
+  if (nq > Lcap) { nq = Lcap; bad = true; }
+  if (L < 0) { L = 0; bad = true; }
+  if (L + nq > Lcap) { L = Lcap - nq; bad = true; }
+  return bad;
+}
+
+inline int check_desc(const bass_attn_desc* d) {
+  if (!d) return BASS_ERR_INVALID_ARG;
+  if (d->B <= 0 || d->kmax <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->D <= 0 || d->Lcap <= 0)
+    return BASS_ERR_INVALID_ARG;
+  if (d->Hq % d->Hkv != 0) return BASS_ERR_INVALID_ARG;
+  if (d->dtype == BASS_DTYPE_BF16) {
+    if (d->D != 64 && d->D != 128) return BASS_ERR_UNSUPPORTED;
+  } else if (d->dtype == BASS_DTYPE_FP32) {
+    if (d->D % 4 != 0 || d->D > 256) return BASS_ERR_UNSUPPORTED;
+  } else {
+    return BASS_ERR_UNSUPPORTED;
+  }
+  // index arithmetic inside the kernels is 32-bit for block counts and 64-bit for bytes
+  if ((int64_t)d->B * d->Hkv * (int64_t)num_blocks(d->Lcap) >= (1ll << 30)) return BASS_ERR_UNSUPPORTED;
+  return BASS_OK;
+}
+
+// Peek, so that the caller can still fetch the HIP error code after a BASS_ERR_HIP return.
+inline int launch_status() { return hipPeekAtLastError() == hipSuccess ? BASS_OK : BASS_ERR_HIP; }
+
+}  // namespace bass

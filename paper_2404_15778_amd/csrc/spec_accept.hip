@@ -1,0 +1,214 @@
+// Speculative-sampling acceptance of libbass: bass_spec_accept.
+//
+// BASS paper, Section 2.2: how many draft tokens are accepted is decided from the
+// probabilities the main and the draft model give them; on rejection a corrected token is
+// sampled from the main model's outputs; the procedure is equivalent to sampling from the
+// main model.  Section 3.2: every sequence stops at its own rejection point.  The rule
+// itself is speculative sampling: accept draft x with probability min(1, p(x)/q(x)); at the
+// first rejection draw from max(p - q, 0) renormalised; after k acceptances draw a bonus
+// token from the next main-model row.
+//
+// Exactness.  The test u < p/q is evaluated as u*q < p in fp64 (the product of two fp32
+// values is exact there).  The draw uses integer weights floor(min(w,1) * 2^44), so sums
+// are associative and the wavefront-parallel reduction order cannot change the result.
+//
+// One workgroup of 16 wavefronts per sequence.  Each wavefront sums 256-entry tiles of the
+// chosen row (pair) with 16-byte loads and keeps the tile sums in LDS; the first wavefront
+// then locates the tile and the entry where the cumulative weight first exceeds the
+// threshold, re-reading only that tile.
+#include "bass_common.h"
+
+namespace bass {
+
+constexpr int kAcceptThreads = 1024;
+constexpr int kAcceptWaves = kAcceptThreads / kWave;
+constexpr int kTile = 256;                    // entries per wavefront tile: 4 per lane
+constexpr int kMaxVocab = 1 << 19;            // keeps the weight sum below 2^63
+constexpr int kMaxTiles = kMaxVocab / kTile;  // 2048
+
+struct AcceptParams {
+  int B, kmax, V;
+  const float* p;
+  const float* q;
+  const int32_t* draft_tok;
+  const int32_t* n_draft;
+  const float* u;
+  int32_t* n_accept;
+  int32_t* next_token;
+  int32_t* ctx_len;
+  int32_t* status;
+};
+
+__device__ inline uint64_t fixed44(float w) {
+  if (!(w > 0.f)) return 0;  // negative residuals and NaN carry no weight
+  double x = (double)w;
+  if (x > 1.0) x = 1.0;
+  return (uint64_t)(x * 17592186044416.0);  // 2^44; truncation = floor for x >= 0
+}
+
+__device__ inline uint64_t wave_sum(uint64_t v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, o);
+  return v;
+}
+
+__device__ inline uint64_t wave_incl_scan64(uint64_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint64_t o = (uint64_t)__shfl_up((unsigned long long)v, d);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// The four weights of entries j0..j0+3 (entries >= V weigh 0).  qrow == nullptr: weights are p.
+__device__ inline void weights4(const float* prow, const float* qrow, int j0, int V, bool vec, uint64_t (&w)[4]) {
+  float pv[4] = {0.f, 0.f, 0.f, 0.f}, qv[4] = {0.f, 0.f, 0.f, 0.f};
+  if (vec && j0 + 3 < V) {
+    const float4 a = *(const float4*)(prow + j0);
+    pv[0] = a.x; pv[1] = a.y; pv[2] = a.z; pv[3] = a.w;
+    if (qrow) {
+      const float4 c = *(const float4*)(qrow + j0);
+      qv[0] = c.x; qv[1] = c.y; qv[2] = c.z; qv[3] = c.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (j0 + e < V) {
+        pv[e] = prow[j0 + e];
+        if (qrow) qv[e] = qrow[j0 + e];
+      }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = fixed44(qrow ? __fsub_rn(pv[e], qv[e]) : pv[e]);
+}
+
+__global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParams a) {
+  __shared__ uint64_t tile_sum[kMaxTiles];
+  __shared__ int sh_first_reject;
+  __shared__ int sh_status;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int V = a.V, kmax = a.kmax;
+  const float* pb = a.p + (size_t)b * (kmax + 1) * V;
+  const float* qb = a.q + (size_t)b * kmax * V;
+  const float* ub = a.u + (size_t)b * (kmax + 1);
+
+  int k = a.n_draft[b];
+  int st = 0;
+  if (k < 0) { k = 0; st |= BASS_STATUS_LEN_CLAMPED; }
+  if (k > kmax) { k = kmax; st |= BASS_STATUS_LEN_CLAMPED; }
+  if (tid == 0) { sh_first_reject = k; sh_status = 0; }
+  __syncthreads();
+
+  // accept tests of all drafts in parallel; the prefix ends at the first rejection
+  for (int i = tid; i < k; i += kAcceptThreads) {
+    int x = a.draft_tok[(size_t)b * kmax + i];
+    if (x < 0) { x = 0; atomicOr(&sh_status, BASS_STATUS_TOKEN_CLAMPED); }
+    if (x >= V) { x = V - 1; atomicOr(&sh_status, BASS_STATUS_TOKEN_CLAMPED); }
+    const double lhs = (double)ub[i] * (double)qb[(size_t)i * V + x];
+    const double rhs = (double)pb[(size_t)i * V + x];
+    if (!(lhs < rhs)) atomicMin(&sh_first_reject, i);
+  }
+  __syncthreads();
+  const int n = sh_first_reject;
+  st |= sh_status;
+
+  const float* prow = pb + (size_t)n * V;
+  const float* qrow = (n < k) ? qb + (size_t)n * V : nullptr;
+  const int ntiles = (V + kTile - 1) / kTile;
+  const bool vec = (V % 4 == 0) && (((uintptr_t)a.p | (uintptr_t)a.q) % 16 == 0);
+
+  uint64_t S = 0;
+  int tok = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    for (int t = wave; t < ntiles; t += kAcceptWaves) {
+      uint64_t w[4];
+      weights4(prow, qrow, t * kTile + 4 * lane, V, vec, w);
+      const uint64_t s = wave_sum(w[0] + w[1] + w[2] + w[3]);
+      if (lane == 0) tile_sum[t] = s;
+    }
+    __syncthreads();
+    // every wavefront derives the total the same way (integer sums: order is irrelevant)
+    uint64_t part = 0;
+    for (int t = lane; t < ntiles; t += 64) part += tile_sum[t];
+    S = wave_sum(part);
+    if (S != 0 || qrow == nullptr) break;
+    qrow = nullptr;  // p <= q everywhere in fp32: the residual has no mass, draw from p itself
+    __syncthreads();
+  }
+
+  if (wave == 0) {
+    if (S == 0) {
+      st |= BASS_STATUS_ZERO_MASS;
+    } else {
+      float ur = ub[kmax];
+      const float umax = 1.0f - 5.9604644775390625e-08f;  // 1 - 2^-24
+      if (!(ur >= 0.f)) ur = 0.f;
+      if (ur > umax) ur = umax;
+      const uint64_t U = (uint64_t)((double)ur * 4294967296.0);
+      // T = (U * S) >> 32 without a 128-bit product: U < 2^32, S < 2^63
+      uint64_t T = U * (S >> 32) + ((U * (S & 0xFFFFFFFFull)) >> 32);
+      // tile holding the first cumulative weight > T: lanes own contiguous runs of tiles
+      const int per = (ntiles + 63) / 64;
+      const int t_lo = lane * per, t_hi = min(ntiles, t_lo + per);
+      uint64_t run = 0;
+      for (int t = t_lo; t < t_hi; ++t) run += tile_sum[t];
+      const uint64_t incl = wave_incl_scan64(run, lane);
+      const uint64_t excl = incl - run;
+      const unsigned long long hit = __ballot(incl > T);
+      const int src = __ffsll((long long)hit) - 1;  // S > T guarantees a hit
+      int tile = 0;
+      uint64_t before = 0;
+      if (lane == src) {
+        uint64_t c = excl;
+        tile = t_lo;
+        for (int t = t_lo; t < t_hi; ++t) {
+          if (c + tile_sum[t] > T) { tile = t; break; }
+          c += tile_sum[t];
+        }
+        before = c;
+      }
+      tile = __shfl(tile, src);
+      before = (uint64_t)__shfl((unsigned long long)before, src);
+      // inside the tile
+      uint64_t w[4];
+      weights4(prow, qrow, tile * kTile + 4 * lane, V, vec, w);
+      const uint64_t mine = w[0] + w[1] + w[2] + w[3];
+      const uint64_t incl2 = before + wave_incl_scan64(mine, lane);
+      const unsigned long long hit2 = __ballot(incl2 > T);
+      const int src2 = __ffsll((long long)hit2) - 1;
+      if (lane == src2) {
+        uint64_t c = incl2 - mine;
+        int e = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (c + w[j] > T) { e = j; break; }
+          c += w[j];
+        }
+        tok = tile * kTile + 4 * lane + e;
+      }
+      tok = __shfl(tok, src2);
+    }
+    if (lane == 0) {
+      a.n_accept[b] = n;
+      a.next_token[b] = tok;
+      if (a.ctx_len) a.ctx_len[b] += n + 1;
+      if (st && a.status) atomicOr(a.status, st);
+    }
+  }
+}
+
+}  // namespace bass
+
+extern "C" int bass_spec_accept(int32_t B, int32_t kmax, int32_t V, const float* p, const float* q,
+                                const int32_t* draft_tok, const int32_t* n_draft, const float* u, int32_t* n_accept,
+                                int32_t* next_token, int32_t* ctx_len, int32_t* dev_status, void* stream) {
+  using namespace bass;
+  if (B <= 0 || kmax < 0 || V <= 0) return BASS_ERR_INVALID_ARG;
+  if (!p || !n_draft || !u || !n_accept || !next_token) return BASS_ERR_INVALID_ARG;
+  if (kmax > 0 && (!q || !draft_tok)) return BASS_ERR_INVALID_ARG;
+  if (V > kMaxVocab) return BASS_ERR_UNSUPPORTED;
+  AcceptParams a{B, kmax, V, p, q, draft_tok, n_draft, u, n_accept, next_token, ctx_len, dev_status};
+  hipLaunchKernelGGL(spec_accept_kernel, dim3((unsigned)B), dim3(kAcceptThreads), 0, (hipStream_t)stream, a);
+  return launch_status();
+}

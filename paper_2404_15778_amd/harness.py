@@ -1,0 +1,98 @@
+"""Device-side plumbing around the binding: uploads numpy inputs, owns caches and workspace.
+
+No arithmetic of the method happens here; every step is a call into libbass.
+bf16 tensors travel as uint16 bit patterns on the numpy side.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import (AttnDesc, alloc_kv_cache, alloc_workspace, bass_kv_append, bass_kv_gather, bass_spec_accept,
+               bass_verify_attention, make_desc)
+
+
+def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy -> torch on the GPU; uint16 arrays are reinterpreted as bf16 bit patterns."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class DeviceAttention:
+    """Caches + workspace of one attention layer for a fixed shape."""
+
+    def __init__(self, B, kmax, Hq, Hkv, D, Lcap, dtype, scale, device="cuda", poison=False):
+        self.desc: AttnDesc = make_desc(B, kmax, Hq, Hkv, D, Lcap, dtype, scale)
+        self.device = device
+        fill = 0xFF if poison else 0  # 0xFF.. is a NaN pattern in bf16 and fp32
+        self.Kc = alloc_kv_cache(self.desc, device, fill)
+        self.Vc = alloc_kv_cache(self.desc, device, fill)
+        self.ws = alloc_workspace(self.desc, device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.O = torch.empty((B, kmax, Hq, D), dtype=torch.float32, device=device)
+        self.lse = torch.empty((B, kmax, Hq), dtype=torch.float32, device=device)
+
+    def append(self, K_rows, V_rows, offset, count):
+        """Write rows [B, n, Hkv, D] (torch, on device) at per-sequence offsets."""
+        d = self.desc.replace(kmax=int(K_rows.shape[1]))
+        bass_kv_append(d, self.Kc, self.Vc, K_rows, V_rows, offset, count, self.status)
+
+    def gather(self, start, count, n):
+        d = self.desc.replace(kmax=int(n))
+        et = torch.bfloat16 if d.dtype == 0 else torch.float32
+        K = torch.zeros((d.B, n, d.Hkv, d.D), dtype=et, device=self.device)
+        V = torch.zeros_like(K)
+        bass_kv_gather(d, self.Kc, self.Vc, K, V, start, count, self.status)
+        return K, V
+
+    def verify(self, Q, ctx_len, draft_len, want_lse=True):
+        bass_verify_attention(self.desc, Q, self.Kc, self.Vc, ctx_len, draft_len, self.O,
+                              self.lse if want_lse else None, self.ws, self.status)
+        return self.O, self.lse
+
+
+def i32(a, device="cuda"):
+    return torch.as_tensor(np.asarray(a, dtype=np.int32), device=device)
+
+
+def run_attention_workload(w, poison=True, device="cuda"):
+    """Whole attention path on a synthetic workload (see workloads.AttnWorkload): fill the cache
+    with the context rows, append the step's own rows, verify.  Returns (O, lse, status) on host."""
+    da = DeviceAttention(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, w.dtype, w.scale, device, poison)
+    K, V = to_device(w.K, device), to_device(w.V, device)
+    ctx, nq = i32(w.ctx_len, device), i32(w.draft_len, device)
+    zero = torch.zeros_like(ctx)
+    da.append(K, V, zero, ctx)  # context (prompt + earlier accepted tokens)
+    # this step's rows, gathered on the host into the [B, kmax, Hkv, D] layout of a model's K/V projection
+    Kn = np.zeros((w.B, w.kmax, w.Hkv, w.D), w.K.dtype)
+    Vn = np.zeros_like(Kn)
+    for b in range(w.B):
+        L, n = int(w.ctx_len[b]), int(w.draft_len[b])
+        Kn[b, :n] = w.K[b, L:L + n]
+        Vn[b, :n] = w.V[b, L:L + n]
+    da.append(to_device(Kn, device), to_device(Vn, device), ctx, nq)
+    O, lse = da.verify(to_device(w.Q, device), ctx, nq)
+    torch.cuda.synchronize()
+    return to_host(O), to_host(lse), int(da.status.item()), da
+
+
+def run_accept_workload(a, ctx_len=None, device="cuda"):
+    """bass_spec_accept on a synthetic workload (see workloads.AcceptWorkload); host results."""
+    B = a.B
+    n_accept = torch.full((B,), -1, dtype=torch.int32, device=device)
+    next_token = torch.full((B,), -1, dtype=torch.int32, device=device)
+    status = torch.zeros(1, dtype=torch.int32, device=device)
+    ctx = None if ctx_len is None else i32(ctx_len, device)
+    bass_spec_accept(to_device(a.p, device), to_device(a.q, device), i32(a.draft_tok, device).reshape(B, a.kmax),
+                     i32(a.n_draft, device), to_device(a.u, device), n_accept, next_token, ctx, status)
+    torch.cuda.synchronize()
+    out = (to_host(n_accept), to_host(next_token), int(status.item()))
+    return out if ctx is None else out + (to_host(ctx),)

@@ -1,0 +1,99 @@
+"""GPU parity: bass_kv_append + bass_verify_attention (through the C ABI) against the fp64 oracle.
+
+Bars (max-abs error of O): 2e-2 for bf16 inputs, 1e-5 for fp32 inputs.  lse is checked to
+the same bars.  Caches are pre-filled with a NaN byte pattern, so any read beyond a
+sequence's valid range shows up as a NaN in the output.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "fp32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2404_15778_amd import harness
+    return harness
+
+
+def check_against_oracle(hip, w, waves=None):
+    import paper_2404_15778_amd as bass
+    if waves is not None:
+        bass.bass_set_attention_waves(waves)
+    try:
+        O, lse, status, _ = hip.run_attention_workload(w, poison=True)
+    finally:
+        bass.bass_set_attention_waves(0)
+    Or, lser = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    assert status == 0
+    assert np.isfinite(O).all() and np.isfinite(lse).all()
+    err = np.abs(O - Or).max()
+    lerr = np.abs(lse - lser).max()
+    print(f"{w.name}: max|O-oracle|={err:.3e} max|lse-oracle|={lerr:.3e}", flush=True)
+    assert err <= TOL[w.dtype], err
+    assert lerr <= TOL[w.dtype], lerr
+    for b in range(w.B):  # unused query slots are exactly zero
+        assert (O[b, int(w.draft_len[b]):] == 0).all() and (lse[b, int(w.draft_len[b]):] == 0).all()
+    return O, lse
+
+
+def test_config1_tiny_fp32(hip):
+    check_against_oracle(hip, wl.config1())
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_small_ragged_bf16(hip, D, seed):
+    # several 32-token blocks, ragged tails, an empty context, an inactive sequence
+    w = wl.make_attention("small_bf16", 5, 4, 4, D, "bf16", [37, 90, 0, 200, 64], [4, 3, 2, 0, 6], seed, kmax=6,
+                          Lcap=300)
+    check_against_oracle(hip, w)
+
+
+@pytest.mark.parametrize("waves", [64, 256, 8192])
+def test_result_does_not_depend_on_the_work_spread(hip, waves):
+    w = wl.make_attention("spread", 3, 4, 2, 128, "bf16", [300, 31, 1000], [5, 1, 3], 3, kmax=5, Lcap=1100)
+    check_against_oracle(hip, w, waves=waves)
+
+
+@pytest.mark.parametrize("g,kmax", [(2, 6), (4, 6), (8, 6), (8, 8)])
+def test_grouped_query_heads_bf16(hip, g, kmax):
+    nq = [kmax, 1, max(1, kmax - 2)]
+    w = wl.make_attention("gqa", 3, 2 * g, 2, 128, "bf16", [150, 33, 257], nq, g, kmax=kmax, Lcap=300)
+    check_against_oracle(hip, w)
+
+
+def test_fp32_grouped_and_wide_heads(hip):
+    w = wl.make_attention("fp32_gqa", 3, 6, 2, 128, "fp32", [70, 0, 130], [3, 2, 5], 5, kmax=5, Lcap=140)
+    check_against_oracle(hip, w)
+    w = wl.make_attention("fp32_many_rows", 2, 4, 1, 32, "fp32", [40, 9], [7, 3], 6, kmax=7, Lcap=64)
+    check_against_oracle(hip, w)  # 28 query rows per kv head: more than one row chunk
+
+
+def test_draft_len_one_is_decode_attention(hip):
+    w = wl.make_attention("decode", 4, 8, 8, 128, "bf16", [511, 512, 513, 31], [1, 1, 1, 1], 7, kmax=1, Lcap=520)
+    check_against_oracle(hip, w)
+
+
+def test_kv_append_then_gather_is_bit_exact(hip):
+    import torch
+    for dtype in ("bf16", "fp32"):
+        w = wl.make_attention("rt", 3, 4, 2, 64, dtype, [45, 0, 97], [3, 2, 4], 8, kmax=4, Lcap=128)
+        _, _, status, da = hip.run_attention_workload(w)
+        total = w.ctx_len + w.draft_len
+        n = int(total.max())
+        K, V = da.gather(hip.i32(np.zeros(w.B)), hip.i32(total), n)
+        torch.cuda.synchronize()
+        K, V = hip.to_host(K), hip.to_host(V)
+        for b in range(w.B):
+            t = int(total[b])
+            np.testing.assert_array_equal(K[b, :t], w.K[b, :t])
+            np.testing.assert_array_equal(V[b, :t], w.V[b, :t])
+        assert status == 0

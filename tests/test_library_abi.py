@@ -1,0 +1,89 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+sizes caches / workspaces on the host, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2404_15778_amd as bass
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built_library():
+    if not os.path.exists(bass.LIB_PATH):
+        from paper_2404_15778_amd import build
+        build.build()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "bass.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bass_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_the_export_list():
+    assert declared_functions() == sorted(bass.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(bass.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(L, name), name
+
+
+def test_version_and_status_strings():
+    assert bass.bass_version() >= 100
+    assert bass.bass_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert bass.bass_status_string(code) not in ("ok", "unknown status")
+
+
+def test_cache_and_workspace_sizes():
+    d = bass.make_desc(8, 6, 32, 32, 128, 2056, "bf16", 0.1)
+    # bf16 caches are stored in whole 32-token blocks
+    assert bass.bass_kv_cache_bytes(d) == 8 * 32 * 65 * 32 * 128 * 2
+    assert bass.bass_verify_attention_workspace_bytes(d) > 0
+    f = bass.make_desc(2, 4, 4, 4, 64, 100, "fp32", 0.125)
+    assert bass.bass_kv_cache_bytes(f) == 2 * 4 * 100 * 64 * 4
+
+
+@pytest.mark.parametrize("kw", [dict(B=0), dict(kmax=0), dict(Hkv=3), dict(Lcap=0), dict(D=0)])
+def test_invalid_shapes_are_rejected_on_the_host(kw):
+    d = bass.make_desc(2, 4, 4, 2, 64, 100, "bf16", 0.125).replace(**kw)
+    assert bass.bass_kv_cache_bytes(d) == 0
+    assert bass.bass_verify_attention_workspace_bytes(d) == 0
+    rc = bass.lib().bass_verify_attention(ctypes.byref(d), None, None, None, None, None, None, None, None, 0, None, None)
+    assert rc == bass.ERR_INVALID_ARG
+
+
+def test_unsupported_shapes():
+    d = bass.make_desc(2, 4, 4, 2, 96, 100, "bf16", 0.125)       # bf16 head size must be 64 or 128
+    assert bass.lib().bass_kv_append(ctypes.byref(d), None, None, None, None, None, None, None, None) == bass.ERR_UNSUPPORTED
+    d = bass.make_desc(2, 4, 4, 2, 64, 100, 7, 0.125)             # unknown dtype
+    assert bass.bass_kv_cache_bytes(d) == 0
+    one = ctypes.c_void_p(16)  # never dereferenced: the checks below fail before any launch
+    d = bass.make_desc(2, 9, 64, 8, 128, 100, "bf16", 0.125)      # 72 query rows per kv head > 64
+    assert bass.lib().bass_verify_attention(ctypes.byref(d), one, one, one, one, one, one, None, one, 1 << 40, None, None) == bass.ERR_UNSUPPORTED
+    assert bass.lib().bass_spec_accept(1, 1, (1 << 19) + 1, one, one, one, one, one, one, one, None, None, None) == bass.ERR_UNSUPPORTED
+
+
+def test_null_pointers_and_small_workspace():
+    d = bass.make_desc(2, 4, 4, 2, 64, 100, "bf16", 0.125)
+    one = ctypes.c_void_p(16)
+    L = bass.lib()
+    assert L.bass_verify_attention(ctypes.byref(d), one, one, None, one, one, one, None, one, 1 << 40, None, None) == bass.ERR_INVALID_ARG
+    assert L.bass_verify_attention(ctypes.byref(d), one, one, one, one, one, one, None, one, 8, None, None) == bass.ERR_WORKSPACE_TOO_SMALL
+    assert L.bass_verify_attention(ctypes.byref(d), one, one, one, one, one, one, None, ctypes.c_void_p(8), 1 << 40, None, None) == bass.ERR_INVALID_ARG
+    assert L.bass_kv_append(ctypes.byref(d), one, one, one, None, one, one, None, None) == bass.ERR_INVALID_ARG
+    assert L.bass_spec_accept(0, 1, 8, one, one, one, one, one, one, one, None, None, None) == bass.ERR_INVALID_ARG
+    assert L.bass_spec_accept(1, 1, 8, one, None, one, one, one, one, one, None, None, None) == bass.ERR_INVALID_ARG
+
+
+def test_attention_waves_knob_is_clamped():
+    assert bass.bass_set_attention_waves(1) == 64
+    assert bass.bass_set_attention_waves(10**6) == 8192
+    assert bass.bass_set_attention_waves(1022) == 1020
+    assert bass.bass_set_attention_waves(0) == 2048
