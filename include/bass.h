@@ -65,8 +65,11 @@ const char* bass_status_string(int code); /* static string, host */
  * bass_kv_append and read back only through bass_kv_gather.  Returns 0 for a bad shape. */
 size_t bass_kv_cache_bytes(const bass_attn_desc* desc);
 
-/* Scratch bytes bass_verify_attention needs for this shape (split-context partial
- * results).  Returns 0 for a bad shape. */
+/* Scratch bytes bass_verify_attention needs for this shape (split-context partial results
+ * and one arrival counter per (sequence, kv head)).  Returns 0 for a bad shape.
+ * The caller ZEROES the workspace once after allocating it; every successful call leaves
+ * the counters at zero again, so the same workspace serves any number of calls (also of
+ * other shapes that fit).  After a failed launch, zero it again. */
 size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* desc);
 
 /*
@@ -112,7 +115,8 @@ int bass_kv_gather(const bass_attn_desc* desc, const void* Kcache, const void* V
  * i >= draft_len[b] of O and lse are written as 0.  ctx_len[b] = 0 is legal.
  * Lengths outside the cache are clamped (BASS_STATUS_LEN_CLAMPED).
  * bf16: kmax * (Hq/Hkv) <= 64.  `workspace` must hold at least
- * bass_verify_attention_workspace_bytes(desc) bytes and be 16-byte aligned.
+ * bass_verify_attention_workspace_bytes(desc) bytes, be 16-byte aligned and have been zeroed
+ * once (see above).  One launch: the split-context reduction runs inside the same kernel.
  */
 int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void* Kcache,
                           const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,

@@ -216,5 +216,6 @@ def alloc_kv_cache(desc, device="cuda", fill_byte=None):
 
 
 def alloc_workspace(desc, device="cuda"):
+    """Attention workspace, zeroed once as the header requires (calls leave its counters zero)."""
     torch = _torch()
-    return torch.empty(bass_verify_attention_workspace_bytes(desc), dtype=torch.uint8, device=device)
+    return torch.zeros(bass_verify_attention_workspace_bytes(desc), dtype=torch.uint8, device=device)

@@ -15,8 +15,9 @@
 // (registers are filled by 1 KiB-contiguous loads of MFMA-ordered cache blocks, next block
 // in flight while the current one is computed), keeps an online softmax (running max and
 // sum per query row) and, for every unit it touches, writes one partial (max, sum,
-// unnormalised output).  A second kernel merges the partials of each unit
-// (split-context reduction) and writes O and the log-sum-exp.
+// unnormalised output).  The wavefront that delivers the LAST partial of a unit (found with
+// one atomic counter per unit) merges the unit's partials -- the split-context reduction --
+// and writes O and the log-sum-exp, so the whole call is a single launch.
 //
 // Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  Tokens sit on the M side:
 //   S^T[16 tokens x 16 query rows] = K[16 x D] * Q^T[D x 16]          (D/32 MFMAs per tile)
@@ -33,6 +34,12 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 static int g_attention_waves = 0;  // 0 = default
+#ifdef BASS_EXP_TRACE
+static long long* g_trace = nullptr;
+#define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
+#else
+#define BASS_TRACE(slot) do { } while (0)
+#endif
 
 static int attention_waves() {
   int w = g_attention_waves > 0 ? g_attention_waves : kDefaultWaves;
@@ -53,7 +60,11 @@ struct AttnParams {
   float* lse;
   float* part_acc;  // [slots][rows_max][D]
   float* part_ml;   // [slots][rows_max][2]  (running max in log2 units, running sum)
+  int32_t* counters;  // [B*Hkv] partials delivered per unit; zero between calls
   int32_t* status;
+#ifdef BASS_EXP_TRACE
+  long long* trace;
+#endif
 };
 
 // ---------------------------------------------------------------------------------------
@@ -75,79 +86,362 @@ __device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bo
   return nq > 0 ? (L + nq + kBlockTokens - 1) / kBlockTokens : 0;
 }
 
-// Sum over sequences of blocks per kv head (wave-uniform).  Raises the status bit once.
-__device__ inline int total_seq_blocks(const AttnParams& p, int lane, bool report) {
-  int total = 0;
-  bool any_bad = false;
-  for (int c0 = 0; c0 < p.B; c0 += 64) {
-    const int b = c0 + lane;
-    int L, nq, nb = 0;
-    bool bad = false;
-    if (b < p.B) nb = seq_blocks(p, b, L, nq, bad);
-    any_bad |= bad;
-    const int inc = wave_incl_scan(nb, lane);
-    total += __shfl(inc, 63);
-  }
-  if (report && p.status && __any(any_bad) && lane == 0) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-  return total;
-}
-
 struct Unit {
   int b, kvh, L, nq, nblk;
   int begin;  // flattened index of the unit's first block
 };
 
-// Unit containing flattened block x (0 <= x < Hkv * total_seq_blocks); wave-uniform.
-__device__ inline Unit locate(const AttnParams& p, int x, int lane) {
-  Unit u{0, 0, 0, 0, 0, 0};
-  int running = 0;
-  for (int c0 = 0; c0 < p.B; c0 += 64) {
+// The schedule of a call, held in registers: lane b keeps sequence b's lengths, block count and
+// inclusive block prefix (first 64 sequences; later ones are re-read when needed).
+struct Sched {
+  int L, nq, nb, inc;
+  int total;  // sum over ALL sequences of blocks per kv head (wave-uniform)
+};
+
+__device__ inline Sched make_sched(const AttnParams& p, int lane, bool report) {
+  Sched s{0, 0, 0, 0, 0};
+  bool any_bad = false;
+  if (lane < p.B) s.nb = seq_blocks(p, lane, s.L, s.nq, any_bad);
+  s.inc = wave_incl_scan(s.nb, lane);
+  s.total = __builtin_amdgcn_readlane(s.inc, 63);
+  for (int c0 = 64; c0 < p.B; c0 += 64) {
     const int b = c0 + lane;
-    int L = 0, nq = 0, nb = 0;
-    bool bad;
+    int L, nq, nb = 0;
+    bool bad = false;
     if (b < p.B) nb = seq_blocks(p, b, L, nq, bad);
-    const int inc = running + wave_incl_scan(nb, lane);
+    any_bad |= bad;
+    s.total += __builtin_amdgcn_readlane(wave_incl_scan(nb, lane), 63);
+  }
+  if (report && p.status && __any(any_bad) && lane == 0) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
+  return s;
+}
+
+// Unit containing flattened block x (0 <= x < Hkv * total); wave-uniform.
+__device__ inline Unit locate(const AttnParams& p, const Sched& s, int x, int lane) {
+  Unit u{0, 0, 0, 0, 0, 0};
+  int c0 = 0, L = s.L, nq = s.nq, nb = s.nb, inc = s.inc;
+  while (true) {
     const unsigned long long hit = __ballot((long long)inc * p.Hkv > (long long)x);
     if (hit) {
       const int src = __ffsll((long long)hit) - 1;
       u.b = c0 + src;
-      u.L = __shfl(L, src);
-      u.nq = __shfl(nq, src);
-      u.nblk = __shfl(nb, src);
-      const int pre = __shfl(inc, src) - u.nblk;
+      u.L = __builtin_amdgcn_readlane(L, src);
+      u.nq = __builtin_amdgcn_readlane(nq, src);
+      u.nblk = __builtin_amdgcn_readlane(nb, src);
+      const int pre = __builtin_amdgcn_readlane(inc, src) - u.nblk;
       u.kvh = (x - pre * p.Hkv) / u.nblk;
       u.begin = pre * p.Hkv + u.kvh * u.nblk;
       return u;
     }
-    running = __shfl(inc, 63);
-  }
-  return u;
-}
-
-// Flattened index of the first block of unit (b, kvh); also returns the unit's lengths.
-__device__ inline Unit unit_of(const AttnParams& p, int b_want, int kvh, int lane) {
-  Unit u{b_want, kvh, 0, 0, 0, 0};
-  int running = 0;
-  for (int c0 = 0; c0 < p.B; c0 += 64) {
+    const int running = __builtin_amdgcn_readlane(inc, 63);
+    c0 += 64;
+    if (c0 >= p.B) return u;  // not reached for x < Hkv * total
     const int b = c0 + lane;
-    int L = 0, nq = 0, nb = 0;
+    L = nq = nb = 0;
     bool bad;
     if (b < p.B) nb = seq_blocks(p, b, L, nq, bad);
-    const int inc = running + wave_incl_scan(nb, lane);
-    if (b_want >= c0 && b_want < c0 + 64) {
-      const int src = b_want - c0;
-      u.L = __shfl(L, src);
-      u.nq = __shfl(nq, src);
-      u.nblk = __shfl(nb, src);
-      u.begin = (__shfl(inc, src) - u.nblk) * p.Hkv + kvh * u.nblk;
-      return u;
-    }
-    running = __shfl(inc, 63);
+    inc = running + wave_incl_scan(nb, lane);
   }
-  return u;
 }
 
 __device__ inline int blocks_per_wave(int total, int nwaves) { return total > 0 ? (total + nwaves - 1) / nwaves : 1; }
+
+// Partials travel between wavefronts that may sit on different XCDs, whose L2 caches are not
+// coherent with each other for ordinary accesses.  Instead of device-scope fences (which write
+// back and invalidate a whole L2 and cost far more than the data is worth), every partial is
+// written and read with device-scope relaxed atomic 64-bit accesses, which go through to the
+// device-coherent level; "wait for my stores, then bump the counter" orders them.
+__device__ inline void store_dev(float* dst, float a, float b) {
+  unsigned long long v = ((unsigned long long)__float_as_uint(b) << 32) | __float_as_uint(a);
+  __hip_atomic_store((unsigned long long*)dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 128-bit variants through raw buffer accesses with the device-scope cache policy (sc1); the
+// buffer descriptor also bounds the access: offsets beyond `bytes` read zero / are dropped.
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+constexpr int kAuxDeviceScope = 16;  // sc1
+
+// base and bytes are wave-uniform by construction; saying so keeps the descriptor in scalar
+// registers (otherwise every access is wrapped in a loop over distinct descriptors).
+__device__ inline __amdgpu_buffer_rsrc_t dev_buffer(const float* base, unsigned bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  float* ub = (float*)(((unsigned long long)hi << 32) | lo);
+  return __builtin_amdgcn_make_buffer_rsrc(ub, 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+
+__device__ inline void store_dev4(__amdgpu_buffer_rsrc_t rs, unsigned byte_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, (int)byte_off, 0, kAuxDeviceScope);
+}
+
+__device__ inline f32x4 load_dev4(__amdgpu_buffer_rsrc_t rs, unsigned byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)byte_off, 0, kAuxDeviceScope));
+}
+
+__device__ inline void store_dev1(float* dst, float a) {
+  __hip_atomic_store((unsigned*)dst, __float_as_uint(a), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline float2 load_dev(const float* src) {
+  const unsigned long long v = __hip_atomic_load((const unsigned long long*)src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
+
+// ---------------------------------------------------------------------------------------
+// Split-context reduction, done by the wavefront that completes a unit:
+//   M = max_s m_s ;  l = sum_s l_s 2^(m_s - M) ;  O = sum_s acc_s 2^(m_s - M) / l
+// over the partials of wavefronts w_lo..w_hi, then zeros for the unit's unused query slots.
+// ---------------------------------------------------------------------------------------
+__device__ inline void zero_rows(const AttnParams& p, int b, int kvh, int row_from, int lane) {
+  const int D = p.D, lpr = D / 4, rpi = 64 / lpr;
+  const int rows_all = p.kmax * p.g;
+  for (int r0 = row_from; r0 < rows_all; r0 += rpi) {
+    const int r = r0 + lane / lpr;
+    if (lane < rpi * lpr && r < rows_all) {
+      const int i = r / p.g, hg = r % p.g;
+      const size_t orow = ((size_t)b * p.kmax + i) * p.Hq + kvh * p.g + hg;
+      *(float4*)(p.O + orow * D + (lane % lpr) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (p.lse && lane % lpr == 0) p.lse[orow] = 0.f;
+    }
+  }
+}
+
+__device__ inline float group16_max(float v) {
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+__device__ inline float group16_sum(float v) {
+#pragma unroll
+  for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Split-context reduction of one unit, eight query rows per sweep: two groups of four rows, 16
+// lanes per row, each lane owning KC float4 chunks of its row.  Two phases, so that the requests
+// of two sweeps can be in flight together:
+//   issue : requests, for the first 8 partials, the row's (max, sum) pairs (every lane of a row
+//           asks for all of them, so no cross-lane traffic is needed later) and the lane's
+//           output chunks -- one round trip to memory in the common case;
+//   finish: weights 2^(m_s - M) / L and the weighted sum, all lane-local; units with more than 8
+//           partials (work spread very thin) continue one partial at a time; writes O and lse.
+// The requests are straight-line code: a request for a partial or a row that does not exist is
+// given an offset beyond the buffer descriptor's size, which the hardware answers with zeros
+// without touching memory.
+template <int KC>
+struct CombineRegs {
+  bool rok[2];
+  int r[2];
+  float2 ml[2][8];
+  f32x4 a[2][8][KC];
+};
+
+struct CombineJob {
+  Unit u;
+  int w_lo, w_hi;
+};
+
+__device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// 2 GiB: larger than any descriptor, and adding a partial's offset, which the host keeps below
+// 2 GiB, cannot wrap around.
+constexpr unsigned kNoSuchOffset = 0x80000000u;
+
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+__device__ inline float2 load_dev2(__amdgpu_buffer_rsrc_t rs, unsigned byte_off) {
+  const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)byte_off, 0, kAuxDeviceScope);
+  return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
+}
+
+template <int KC, int DC>
+__device__ inline void combine_issue(const AttnParams& p, const CombineJob& job, int r0, int lane, CombineRegs<KC>& c) {
+  const Unit& u = job.u;
+  const int D = DC > 0 ? DC : p.D;
+  const int rr = lane >> 4, dl = lane & 15;
+  const int rows = uniform(u.nq * p.g);
+  const int S8 = min(uniform(job.w_hi - job.w_lo + 1), 8);
+  const size_t slot0 = (size_t)uniform(job.w_lo + u.b * p.Hkv + u.kvh);
+  const unsigned slot_bytes = (unsigned)p.rows_max * D * 4, ml_bytes = (unsigned)p.rows_max * 8;
+  const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S8 * slot_bytes);
+  const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S8 * ml_bytes);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    c.rok[q] = r0 + 4 * q + rr < rows;
+    c.r[q] = r0 + 4 * q + rr;
+    const unsigned ml_off = c.rok[q] ? (unsigned)c.r[q] * 8 : kNoSuchOffset;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c.ml[q][j] = load_dev2(rs_ml, (unsigned)j * ml_bytes + ml_off);
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      const int d = 4 * (dl + 16 * k);
+      const unsigned row_off = (c.rok[q] && d < D) ? (unsigned)(c.r[q] * D + d) * 4 : kNoSuchOffset;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) c.a[q][j][k] = load_dev4(rs, (unsigned)j * slot_bytes + row_off);
+    }
+  }
+}
+
+template <int KC, int DC>
+__device__ inline void combine_finish(const AttnParams& p, const CombineJob& job, int r0, int lane, const CombineRegs<KC>& c) {
+  const Unit& u = job.u;
+  const int D = DC > 0 ? DC : p.D;
+  const int dl = lane & 15;
+  const int S = uniform(job.w_hi - job.w_lo + 1);
+  const size_t slot0 = (size_t)uniform(job.w_lo + u.b * p.Hkv + u.kvh);
+  const unsigned slot_bytes = (unsigned)p.rows_max * D * 4, ml_bytes = (unsigned)p.rows_max * 8;
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int r = c.r[q];
+    // M = max_s m_s, L = sum_s l_s 2^(m_s - M).  A valid row has at least one partial with a
+    // visible token (token 0), so M ends finite; a partial that saw none has m = -inf, weight 0.
+    float m[8];
+    float M = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      m[j] = (j < S) ? c.ml[q][j].x : -INFINITY;  // requests beyond the last partial came back as zeros
+      M = fmaxf(M, m[j]);
+    }
+    const unsigned row8 = c.rok[q] ? (unsigned)r * 8 : kNoSuchOffset;
+    if (S > 8) {
+      const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
+#pragma unroll 1
+      for (int j = 8; j < S; ++j) M = fmaxf(M, load_dev2(rs_ml, (unsigned)j * ml_bytes + row8).x);
+    }
+    const float Mf = (M == -INFINITY) ? 0.f : M;  // idle row slots only
+    float wgt[8];
+    float L = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      wgt[j] = __builtin_amdgcn_exp2f(m[j] - Mf);
+      L = fmaf(c.ml[q][j].y, wgt[j], L);
+    }
+    f32x4 acc[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) acc[k] = zero4;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int k = 0; k < KC; ++k) acc[k] += c.a[q][j][k] * wgt[j];
+    if (S > 8) {  // further partials, one at a time
+      const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S * slot_bytes);
+      const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
+#pragma unroll 1
+      for (int j = 8; j < S; ++j) {
+        const float2 ml = load_dev2(rs_ml, (unsigned)j * ml_bytes + row8);
+        const float w = __builtin_amdgcn_exp2f(ml.x - Mf);
+        L = fmaf(ml.y, w, L);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+          const int d = 4 * (dl + 16 * k);
+          const unsigned row_off = (c.rok[q] && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
+          acc[k] += load_dev4(rs, (unsigned)j * slot_bytes + row_off) * w;
+        }
+      }
+    }
+    if (c.rok[q]) {
+      const float invL = 1.f / L;
+      const int i = r / p.g, hg = r % p.g;
+      const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int d = 4 * (dl + 16 * k);
+        if (d < D) *(f32x4*)(p.O + orow * D + d) = acc[k] * invL;
+      }
+      if (p.lse && dl == 0) p.lse[orow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+    }
+  }
+}
+
+// Reduction of the one or two units this wavefront completed.  The sweeps (8 rows each) of both
+// jobs are laid end to end and handled two at a time, so that two sweeps -- typically the only
+// sweep of each unit -- share one round trip to memory.
+template <int KC, int DC>
+__device__ inline void combine_jobs(const AttnParams& p, const CombineJob& ja, bool do_a, const CombineJob& jb, bool do_b,
+                                    int lane, int wdbg = 0) {
+  constexpr bool kOverlap = DC > 0;  // the run-time-D (fp32) variant has too many chunk registers for two sweeps
+  const CombineJob& j0 = do_a ? ja : jb;  // first (or only) job
+  const bool two = do_a && do_b;
+  const int n0 = (j0.u.nq * p.g + 7) / 8;
+  const int n1 = two ? (jb.u.nq * p.g + 7) / 8 : 0;
+#pragma unroll 1
+  for (int t = 0; t < n0 + n1; t += (kOverlap ? 2 : 1)) {
+    const bool has_y = kOverlap && t + 1 < n0 + n1;
+    const CombineJob jx = (t < n0) ? j0 : jb;
+    const int rx = (t < n0) ? 8 * t : 8 * (t - n0);
+    const CombineJob jy = (t + 1 < n0) ? j0 : jb;
+    const int ry = (t + 1 < n0) ? 8 * (t + 1) : 8 * (t + 1 - n0);
+    CombineRegs<KC> cx;
+    combine_issue<KC, DC>(p, jx, rx, lane, cx);
+    if constexpr (kOverlap) {
+      CombineRegs<KC> cy;
+      if (has_y) combine_issue<KC, DC>(p, jy, ry, lane, cy);
+#ifdef BASS_EXP_TRACE
+      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 8] = wall_clock64();
+      { float probe = cx.a[0][0][0][0] + cx.ml[0][0].x; asm volatile("" :: "v"(probe)); }
+      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 9] = wall_clock64();
+#endif
+      combine_finish<KC, DC>(p, jx, rx, lane, cx);
+#ifdef BASS_EXP_TRACE
+      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 10] = wall_clock64();
+#endif
+      if (has_y) combine_finish<KC, DC>(p, jy, ry, lane, cy);
+    } else {
+      combine_finish<KC, DC>(p, jx, rx, lane, cx);
+    }
+  }
+}
+
+// All of this wavefront's partial stores have reached the device-coherent level once their
+// acknowledgements are back; only then may its arrival be counted.
+__device__ inline void partial_stores_done() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
+// Counts this wavefront's arrival at one or two units (after partial_stores_done).  A job's
+// `last` result is true if this wavefront delivered the unit's last partial: it then owns the
+// reduction over wavefronts w_lo..w_hi.  Both counters are bumped before either result is awaited.
+__device__ inline int32_t* arrival_counter(const AttnParams& p, int c, CombineJob& j, int& nparts) {
+  j.w_lo = j.u.begin / c;
+  j.w_hi = (j.u.begin + j.u.nblk - 1) / c;
+  nparts = j.w_hi - j.w_lo + 1;
+  return p.counters + (size_t)j.u.b * p.Hkv + j.u.kvh;
+}
+
+__device__ inline void arrive(const AttnParams& p, int c, int lane, CombineJob& ja, bool& last_a, bool has_b, CombineJob& jb,
+                              bool& last_b) {
+  int na, nb = 1, old_a = 0, old_b = 0;
+  int32_t* ctr_a = arrival_counter(p, c, ja, na);
+  int32_t* ctr_b = ctr_a;
+  if (has_b) ctr_b = arrival_counter(p, c, jb, nb);
+  if (na > 1 && lane == 0) old_a = __hip_atomic_fetch_add(ctr_a, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (has_b && nb > 1 && lane == 0) old_b = __hip_atomic_fetch_add(ctr_b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  last_a = na == 1 || __builtin_amdgcn_readfirstlane(old_a) == na - 1;
+  last_b = has_b && (nb == 1 || __builtin_amdgcn_readfirstlane(old_b) == nb - 1);
+  // every contributor has arrived: leave the counter clean for the next call
+  if (last_a && na > 1 && lane == 0) __hip_atomic_store(ctr_a, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (last_b && nb > 1 && lane == 0) __hip_atomic_store(ctr_b, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
+// They belong to no wavefront's share of blocks, so wavefront w clears them for the units
+// w, w + nwaves, ... right at the start, off the critical path.
+__device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int lane) {
+  for (int unit = w; unit < p.B * p.Hkv; unit += p.nwaves) {
+    const int b = unit / p.Hkv;
+    int nq;
+    if (b < 64) {
+      nq = __builtin_amdgcn_readlane(s.nq, b);
+    } else {
+      int L;
+      bool bad;
+      seq_blocks(p, b, L, nq, bad);
+    }
+    zero_rows(p, b, unit % p.Hkv, nq * p.g, lane);
+  }
+}
 
 // ---------------------------------------------------------------------------------------
 // bf16 streaming kernel
@@ -158,12 +452,13 @@ struct KvRegs {
   uint4 v[D / 16];
 };
 
+// kb, vb already include the lane offset
 template <int D>
-__device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb, int lane) {
+__device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb) {
 #pragma unroll
-  for (int i = 0; i < 2 * (D / 32); ++i) r.k[i] = kb[i * 64 + lane];
+  for (int i = 0; i < 2 * (D / 32); ++i) r.k[i] = kb[i * 64];
 #pragma unroll
-  for (int i = 0; i < D / 16; ++i) r.v[i] = vb[i * 64 + lane];
+  for (int i = 0; i < D / 16; ++i) r.v[i] = vb[i * 64];
 }
 
 template <int D, int NT>
@@ -256,85 +551,184 @@ __device__ inline void block_dispatch(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 3
 }
 
 template <int D, int NT>
+struct QFrag {
+  bf16x8 q[NT][D / 32];  // B operand: lane (col, grp) holds query row 16 nt + col, elements 32 t + 8 grp .. +7
+  int lim[NT];           // last token visible to that row
+};
+
+template <int D, int NT>
+__device__ inline void load_queries(const AttnParams& p, const Unit& u, bool enable, int col, int grp, QFrag<D, NT>& f) {
+  const int rows = u.nq * p.g;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int rrow = nt * 16 + col;
+    const bool ok = enable && rrow < rows;
+    const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
+    f.lim[nt] = u.L + i;
+    const uint4* qrow = (const uint4*)((const uint16_t*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D);
+#pragma unroll
+    for (int t = 0; t < D / 32; ++t) {
+      uint4 qv = make_uint4(0, 0, 0, 0);
+      if (ok) qv = qrow[t * 4 + grp];
+      f.q[nt][t] = __builtin_bit_cast(bf16x8, qv);
+    }
+  }
+}
+
+template <int D, int NT>
+__device__ inline void clear_state(RowState<D, NT>& st) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    st.m[nt] = -INFINITY;
+    st.l[nt] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < D / 16; ++mt) st.acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
+// Partial of (wavefront w, unit u): slot ids w + unit are unique because both grow monotonically
+// along the flattened list.
+template <int D, int NT>
+__device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, const RowState<D, NT>& st, int col, int grp) {
+  const int rows = u.nq * p.g;
+  const size_t slot = (size_t)w + (size_t)u.b * p.Hkv + u.kvh;
+  const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot * p.rows_max * D, (unsigned)p.rows_max * D * 4);
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float l = st.l[nt];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int rrow = nt * 16 + col;
+    if (rrow < rows) {
+      const unsigned off = (unsigned)(rrow * D + 4 * grp) * 4;
+#pragma unroll
+      for (int mt = 0; mt < D / 16; ++mt) store_dev4(rs, off + 64 * mt, st.acc[nt][mt]);
+      if (grp == 0) store_dev(p.part_ml + (slot * p.rows_max + rrow) * 2, st.m[nt], l);
+    }
+  }
+}
+
+template <int D, int NT>
 __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
-  constexpr int KS = D / 32, MT = D / 16;
-  constexpr size_t kBlkVec = (size_t)kBlockTokens * D * 2 / 16;  // uint4 per block
+  constexpr ptrdiff_t kBlkVec = (ptrdiff_t)kBlockTokens * D * 2 / 16;  // uint4 per block
+  // With one query tile there are registers to spare for a second unit's state, so a wavefront
+  // whose share of blocks crosses a unit boundary keeps streaming: it parks the first unit's
+  // accumulators, carries on with the second unit, and delivers both partials at the end.
+  constexpr bool kPair = (NT == 1);
   const int lane = threadIdx.x & 63;
   const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int col = lane & 15, grp = lane >> 4;
+  BASS_TRACE(0);
 
-  const int total = total_seq_blocks(p, lane, w == 0) * p.Hkv;
+  const Sched sched = make_sched(p, lane, w == 0);
+  const int total = sched.total * p.Hkv;
   const int c = blocks_per_wave(total, p.nwaves);
   int x = w * c;
   const int x_end = min(total, x + c);
+  zero_unused_rows(p, sched, w, lane);
+  BASS_TRACE(1);
 
   while (x < x_end) {
-    const Unit u = locate(p, x, lane);
-    const int blk0 = x - u.begin;
-    const int nseg = min(x_end, u.begin + u.nblk) - x;  // blocks of this unit that are ours
-    const int rows = u.nq * p.g;                         // valid query rows of the unit
-    const int n_valid = u.L + u.nq;
-
-    // query fragments (B operand): lane (col, grp) holds row 16 nt + col, elements 32 t + 8 grp ..+7
-    bf16x8 qf[NT][KS];
-    int lim[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int rrow = nt * 16 + col;
-      const bool ok = rrow < rows;
-      const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
-      lim[nt] = u.L + i;
-      const uint4* qrow = (const uint4*)((const uint16_t*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D);
-#pragma unroll
-      for (int t = 0; t < KS; ++t) {
-        uint4 qv = make_uint4(0, 0, 0, 0);
-        if (ok) qv = qrow[t * 4 + grp];
-        qf[nt][t] = __builtin_bit_cast(bf16x8, qv);
+    const Unit uA = locate(p, sched, x, lane);
+    const int nA = min(x_end, uA.begin + uA.nblk) - x;  // blocks of unit A that are ours
+    Unit uB = uA;
+    int nB = 0;
+    bool hasB = false;
+    if constexpr (kPair) {
+      if (x + nA < x_end) {
+        hasB = true;
+        uB = locate(p, sched, x + nA, lane);  // starts at its block 0
+        nB = min(x_end, uB.begin + uB.nblk) - (x + nA);
       }
     }
+    const int n = nA + nB;
+    BASS_TRACE(2);
 
-    RowState<D, NT> st;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      st.m[nt] = -INFINITY;
-      st.l[nt] = 0.f;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) st.acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    QFrag<D, NT> qc, qB;
+    load_queries<D, NT>(p, uA, true, col, grp, qc);
+    if constexpr (kPair) load_queries<D, NT>(p, uB, hasB, col, grp, qB);
 
-    const size_t unit_vec = ((size_t)u.b * p.Hkv + u.kvh) * p.nblk_cap * kBlkVec;
-    const uint4* kbase = (const uint4*)p.Kc + unit_vec;
-    const uint4* vbase = (const uint4*)p.Vc + unit_vec;
+    RowState<D, NT> st, parked;
+    clear_state<D, NT>(st);
+    int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
 
-    KvRegs<D> ra, rb;
-    load_block<D>(ra, kbase + (size_t)blk0 * kBlkVec, vbase + (size_t)blk0 * kBlkVec, lane);
-    for (int s = 0; s < nseg; s += 2) {
-      const int blk = blk0 + s;
-      if (s + 1 < nseg) load_block<D>(rb, kbase + (size_t)(blk + 1) * kBlkVec, vbase + (size_t)(blk + 1) * kBlkVec, lane);
-      block_dispatch<D, NT>(ra, qf, st, blk, u.L, n_valid, lim, p.scale_log2, lane);
-      if (s + 1 < nseg) {
-        if (s + 2 < nseg) load_block<D>(ra, kbase + (size_t)(blk + 2) * kBlkVec, vbase + (size_t)(blk + 2) * kBlkVec, lane);
-        block_dispatch<D, NT>(rb, qf, st, blk + 1, u.L, n_valid, lim, p.scale_log2, lane);
+    // element offsets (in uint4) of step s inside the K and V caches
+    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + (x - uA.begin)) * kBlkVec;
+    const ptrdiff_t vecB = (((ptrdiff_t)uB.b * p.Hkv + uB.kvh) * p.nblk_cap - nA) * kBlkVec;
+    const uint4* kc = (const uint4*)p.Kc;
+    const uint4* vc = (const uint4*)p.Vc;
+
+    // Every fetch is issued unconditionally so that the wait counts before each compute step are
+    // exact (a fetch under a branch would force a wait for ALL outstanding loads at the join and
+    // serialise load and compute).  A fetch past the end of the share reads 16 bytes of the
+    // share's first block with every lane instead: valid memory, one cache line, never used.
+    auto fetch = [&](KvRegs<D>& r, int s) {
+      ptrdiff_t off = vecA;
+      if (s < n) off = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec + lane;
+      load_block<D>(r, kc + off, vc + off);
+    };
+    auto step = [&](KvRegs<D>& r, int s) {
+      if constexpr (kPair) {
+        if (s == nA) {  // first block of unit B: park A's state (register moves only)
+          parked = st;
+          clear_state<D, NT>(st);
+          qc = qB;
+          cur_L = uB.L;
+          cur_valid = uB.L + uB.nq;
+          cur_blk = -nA;
+        }
+      }
+#ifdef BASS_EXP_NOCOMPUTE
+      unsigned xx = 0;
+      for (int i = 0; i < 2 * (D / 32); ++i) xx ^= r.k[i].x ^ r.k[i].y ^ r.k[i].z ^ r.k[i].w;
+      for (int i = 0; i < D / 16; ++i) xx ^= r.v[i].x ^ r.v[i].y ^ r.v[i].z ^ r.v[i].w;
+      st.l[0] += __uint_as_float(xx & 0x3f800000u);
+#else
+      block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane);
+#endif
+    };
+    if constexpr (NT <= 2) {
+      // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
+      KvRegs<D> r0, r1, r2;
+      fetch(r0, 0);
+      fetch(r1, 1);
+      for (int s = 0; s < n; s += 3) {
+        fetch(r2, s + 2);
+        step(r0, s);
+        fetch(r0, s + 3);
+        if (s + 1 < n) step(r1, s + 1);
+        fetch(r1, s + 4);
+        if (s + 2 < n) step(r2, s + 2);
+      }
+    } else {
+      // many query rows need the registers for accumulators: two-deep ring
+      KvRegs<D> r0, r1;
+      fetch(r0, 0);
+      for (int s = 0; s < n; s += 2) {
+        fetch(r1, s + 1);
+        step(r0, s);
+        fetch(r0, s + 2);
+        if (s + 1 < n) step(r1, s + 1);
       }
     }
+    BASS_TRACE(3);
 
-    // partial of this (wave, unit) pair; slot ids w + unit are unique because both grow
-    // monotonically along the flattened list
-    const size_t slot = (size_t)w + (size_t)u.b * p.Hkv + u.kvh;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      float l = st.l[nt];
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
-      const int rrow = nt * 16 + col;
-      if (rrow < rows) {
-        float* dst = p.part_acc + (slot * p.rows_max + rrow) * D + 4 * grp;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) *(f32x4*)(dst + 16 * mt) = st.acc[nt][mt];
-        if (grp == 0) *(float2*)(p.part_ml + (slot * p.rows_max + rrow) * 2) = make_float2(st.m[nt], l);
-      }
-    }
-    x += nseg;
+    if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
+    store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
+    partial_stores_done();
+    BASS_TRACE(4);
+    CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};
+    bool lastA, lastB;
+    arrive(p, c, lane, ja, lastA, hasB, jb, lastB);
+    BASS_TRACE(5);
+#ifdef BASS_EXP_TRACE
+    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
+#endif
+#ifndef BASS_EXP_NOCOMBINE
+    if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane, w);
+#endif
+    BASS_TRACE(6);
+    x += n;
   }
 }
 
@@ -351,13 +745,15 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
   const int D = p.D;
   const int nd = (D + 63) / 64;  // head elements per lane (<= 4)
 
-  const int total = total_seq_blocks(p, lane, w == 0) * p.Hkv;
+  const Sched sched = make_sched(p, lane, w == 0);
+  const int total = sched.total * p.Hkv;
   const int c = blocks_per_wave(total, p.nwaves);
   int x = w * c;
   const int x_end = min(total, x + c);
+  zero_unused_rows(p, sched, w, lane);
 
   while (x < x_end) {
-    const Unit u = locate(p, x, lane);
+    const Unit u = locate(p, sched, x, lane);
     const int blk0 = x - u.begin;
     const int nseg = min(x_end, u.begin + u.nblk) - x;
     const int rows = u.nq * p.g;
@@ -439,73 +835,36 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
           float* dst = p.part_acc + (slot * p.rows_max + rrow) * D;
 #pragma unroll
           for (int k = 0; k < 4; ++k)
-            if (k < nd && lane + 64 * k < D) dst[lane + 64 * k] = acc[r][k];
-          if (lane == 0) *(float2*)(p.part_ml + (slot * p.rows_max + rrow) * 2) = make_float2(m[r], l[r]);
+            if (k < nd && lane + 64 * k < D) store_dev1(dst + lane + 64 * k, acc[r][k]);
+          if (lane == 0) store_dev(p.part_ml + (slot * p.rows_max + rrow) * 2, m[r], l[r]);
         }
       }
     }
+    partial_stores_done();
+    CombineJob job{u, 0, 0};
+    bool last, unused;
+    arrive(p, c, lane, job, last, false, job, unused);
+    if (last) combine_jobs<4, 0>(p, job, true, job, false, lane);
     x += nseg;
   }
 }
 
-// ---------------------------------------------------------------------------------------
-// Split-context reduction: one wavefront per output row (b, i, hq).
-//   M = max_s m_s ;  l = sum_s l_s 2^(m_s - M) ;  O = sum_s acc_s 2^(m_s - M) / l
-// ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void combine_partials(AttnParams p) {
-  const int lane = threadIdx.x & 63;
-  const long row_id = (long)blockIdx.x * 4 + (threadIdx.x >> 6);  // over [B][kmax][Hq]
-  if (row_id >= (long)p.B * p.kmax * p.Hq) return;
-  const int hq = (int)(row_id % p.Hq);
-  const int i = (int)((row_id / p.Hq) % p.kmax);
-  const int b = (int)(row_id / ((long)p.Hq * p.kmax));
-  const int D = p.D;
-  float* out = p.O + (size_t)row_id * D;
-  const int kvh = hq / p.g, hg = hq % p.g;
-  const Unit u = unit_of(p, b, kvh, lane);
-  if (i >= u.nq) {
-    for (int d = lane; d < D; d += 64) out[d] = 0.f;
-    if (p.lse && lane == 0) p.lse[row_id] = 0.f;
-    return;
-  }
-  const int total = total_seq_blocks(p, lane, false) * p.Hkv;
-  const int c = blocks_per_wave(total, p.nwaves);
-  const int w_lo = u.begin / c, w_hi = (u.begin + u.nblk - 1) / c;
-  const int rrow = i * p.g + hg;
-  const size_t unit_id = (size_t)b * p.Hkv + kvh;
-
-  float M = -INFINITY;
-  for (int w = w_lo + lane; w <= w_hi; w += 64)
-    M = fmaxf(M, p.part_ml[((w + unit_id) * p.rows_max + rrow) * 2]);
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
-
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-  for (int w = w_lo; w <= w_hi; ++w) {
-    const size_t pr = (w + unit_id) * p.rows_max + rrow;
-    const float2 ml = *(const float2*)(p.part_ml + pr * 2);
-    const float wgt = exp2f(ml.x - M);  // a partial without visible tokens has m = -inf, weight 0
-    l = fmaf(ml.y, wgt, l);
-    const float* src = p.part_acc + pr * D;
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-      if (lane + 64 * k < D) acc[k] = fmaf(src[lane + 64 * k], wgt, acc[k]);
-  }
-  const float inv = 1.f / l;
-#pragma unroll
-  for (int k = 0; k < 4; ++k)
-    if (lane + 64 * k < D) out[lane + 64 * k] = acc[k] * inv;
-  if (p.lse && lane == 0) p.lse[row_id] = (M + log2f(l)) * 0.6931471805599453f;
+// Workspace = [unit counters, padded to 256 B][partial outputs][partial (max, sum) pairs].
+static size_t counter_bytes(const bass_attn_desc* d) {
+  return (((size_t)d->B * d->Hkv * sizeof(int32_t)) + 255) & ~(size_t)255;
 }
 
 static size_t workspace_bytes(const bass_attn_desc* d) {
   const size_t slots = (size_t)kMaxWaves + (size_t)d->B * d->Hkv;
   const size_t rows = (size_t)d->kmax * (d->Hq / d->Hkv);
-  return slots * rows * ((size_t)d->D + 2) * sizeof(float);
+  return counter_bytes(d) + slots * rows * ((size_t)d->D + 2) * sizeof(float);
 }
 
 }  // namespace bass
+
+#ifdef BASS_EXP_TRACE
+extern "C" void bass_debug_set_trace(void* ptr) { bass::g_trace = (long long*)ptr; }
+#endif
 
 extern "C" int bass_set_attention_waves(int waves) {
   bass::g_attention_waves = waves > 0 ? waves : 0;
@@ -528,6 +887,8 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
   const int g = d->Hq / d->Hkv;
   const int rows_max = d->kmax * g;
   if (d->dtype == BASS_DTYPE_BF16 && rows_max > 64) return BASS_ERR_UNSUPPORTED;
+  // partials of one unit are addressed with 32-bit byte offsets
+  if ((int64_t)rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
   if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
 
   AttnParams p;
@@ -536,8 +897,12 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
   p.scale_log2 = d->scale * 1.4426950408889634f;
   p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.ctx_len = ctx_len; p.draft_len = draft_len;
   p.O = O; p.lse = lse; p.status = dev_status;
+#ifdef BASS_EXP_TRACE
+  p.trace = g_trace;
+#endif
   const size_t slots = (size_t)kMaxWaves + (size_t)d->B * d->Hkv;
-  p.part_acc = (float*)workspace;
+  p.counters = (int32_t*)workspace;
+  p.part_acc = (float*)((char*)workspace + counter_bytes(d));
   p.part_ml = p.part_acc + slots * rows_max * d->D;
 
   hipStream_t s = (hipStream_t)stream;
@@ -556,8 +921,5 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
     }
 #undef BASS_LAUNCH
   }
-  if (launch_status() != BASS_OK) return BASS_ERR_HIP;
-  const long out_rows = (long)d->B * d->kmax * d->Hq;
-  hipLaunchKernelGGL(combine_partials, dim3((unsigned)((out_rows + 3) / 4)), dim3(256), 0, s, p);
   return launch_status();
 }
