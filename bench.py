@@ -2,10 +2,10 @@
 """Benchmark of the BASS verification step on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch of synthetic input shaped like
-the paper's 7.8B / batch-8 workload: for each of 32 attention layers, bass_kv_append of the
-step's K/V rows followed by bass_verify_attention (ragged, B=8, Hq=Hkv=32, D=128, bf16,
-ctx ~ U{512..2048}, drafts ~ U{1..6}), then one bass_spec_accept over a 50k vocabulary
-(k=5).  Every layer has its own cache slab, so the KV reads of a step (~5 GB) cannot be
+the paper's 7.8B / batch-8 workload: for each of 32 attention layers, the append of the
+step's K/V rows and the ragged verify attention (bass_append_verify_attention, one launch;
+B=8, Hq=Hkv=32, D=128, bf16, ctx ~ U{512..2048}, drafts ~ U{1..6}), then one
+bass_spec_accept over a 50k vocabulary (k=5).  Every layer has its own cache slab, so the KV reads of a step (~5 GB) cannot be
 served from the 256 MB last-level cache.
 
 Prints ONE JSON line.  `value` = algorithmic KV bytes of the step (every valid K and V row
@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=32, help="attention layers (independent cache slabs) per step")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0, help="override the attention work spread (0 = library default)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
+    ap.add_argument("--separate-append", action="store_true", help="bass_kv_append + bass_verify_attention as two launches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -101,10 +103,14 @@ def main():
 
     def step(events=None):
         for li, l in enumerate(layers):
-            bass.bass_kv_append(desc, l["Kc"], l["Vc"], l["Kn"], l["Vn"], ctx, nq, status)
             if events is not None:
                 events[li][0].record()
-            bass.bass_verify_attention(desc, l["Q"], l["Kc"], l["Vc"], ctx, nq, O, None, ws, status)
+            if args.separate_append:
+                bass.bass_kv_append(desc, l["Kc"], l["Vc"], l["Kn"], l["Vn"], ctx, nq, status)
+                bass.bass_verify_attention(desc, l["Q"], l["Kc"], l["Vc"], ctx, nq, O, None, ws, status)
+            else:  # append of the step's K/V rows fused into the attention launch
+                bass.bass_append_verify_attention(desc, l["Q"], l["Kn"], l["Vn"], l["Kc"], l["Vc"], ctx, nq, O, None,
+                                                  ws, status)
             if events is not None:
                 events[li][1].record()
         if events is not None:
@@ -113,12 +119,35 @@ def main():
         if events is not None:
             events[NL][1].record()
 
+    # One step is 2 * layers + 1 launches of 3-40 us each; a serving loop replays them as a HIP graph so
+    # that the CPU's launch cost does not pace the GPU.  (The library itself records no memset nodes.)
+    run_step = step
+    if not args.no_graph:
+        step()  # eager reference for the replay check below
+        torch.cuda.synchronize()
+        O_ref, nacc_ref, tok_ref = O.clone(), n_accept.clone(), next_token.clone()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):  # every replay must reproduce the eager result bit for bit
+            O.zero_()
+            n_accept.fill_(-1)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(O, O_ref) and torch.equal(n_accept, nacc_ref) and torch.equal(next_token, tok_ref), \
+                "graph replay differs from eager execution"
+        run_step = graph.replay
+
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert int(status.item()) == 0, "device status word is not clean"
@@ -158,6 +187,8 @@ def main():
             "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "layers": NL, "seed": args.seed,
             "ctx_len": w.ctx_len.tolist(), "draft_len": w.draft_len.tolist(),
             "kv_bytes_per_layer": kv_bytes, "attention_waves": bass.bass_set_attention_waves(args.waves),
+            "launch": "eager" if args.no_graph else "hip_graph_replay",
+            "append": "separate launch" if args.separate_append else "fused into the attention launch",
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "verified_tokens_per_s": round(w.verified_tokens / (wall / args.steps), 1),
@@ -165,7 +196,7 @@ def main():
         "attention_call_us": round(attn_us, 2),
         "spec_accept_us": round(accept_us, 2),
         "roofline": {
-            "kernel": "verify_attn_bf16<128,1> (+ split-context combine, same call)",
+            "kernel": "verify_attn_bf16<128,1> (append + streaming + split-context reduction, one launch)",
             "bound": "hbm",
             "achieved": round(kv_bytes / (attn_us * 1e-6) / 1e9, 1),
             "peak": HBM_PEAK_GBPS,

@@ -124,6 +124,20 @@ int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void*
                           int32_t* dev_status, void* stream);
 
 /*
+ * The two calls above in ONE launch: appends rows i < draft_len[b] of K_new, V_new
+ * [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
+ * bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, ...) would, and computes
+ * bass_verify_attention over the updated caches.  Results (O, lse, cache contents) are identical
+ * to the two separate calls.  Rows of sequences whose lengths had to be clamped are appended at
+ * the clamped positions.  Arguments as in those calls.
+ */
+int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, const void* K_new,
+                                 const void* V_new, void* Kcache, void* Vcache,
+                                 const int32_t* ctx_len, const int32_t* draft_len, float* O,
+                                 float* lse, void* workspace, size_t workspace_bytes,
+                                 int32_t* dev_status, void* stream);
+
+/*
  * Speculative-sampling acceptance for the batch (Section 2.2: the number of accepted
  * drafts is decided from the main- and draft-model probabilities; on rejection a corrected
  * token is sampled from the main model's outputs; the procedure is equivalent to sampling

@@ -22,7 +22,8 @@ DTYPE_BF16, DTYPE_FP32 = 0, 1
 # every symbol include/bass.h declares
 EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
-    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_spec_accept", "bass_set_attention_waves",
+    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_append_verify_attention", "bass_spec_accept",
+    "bass_set_attention_waves",
 )
 
 
@@ -69,6 +70,8 @@ def lib():
         L.bass_kv_gather.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_verify_attention.restype = ctypes.c_int
         L.bass_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+        L.bass_append_verify_attention.restype = ctypes.c_int
+        L.bass_append_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_spec_accept.restype = ctypes.c_int
         L.bass_spec_accept.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_set_attention_waves.restype = ctypes.c_int
@@ -187,6 +190,23 @@ def bass_verify_attention(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, w
         _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
         ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
         _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_verify_attention")
+
+
+def bass_append_verify_attention(desc, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                 dev_status=None, stream=None):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    rows = (desc.B, desc.kmax, desc.Hkv, desc.D)
+    et = _elt_dtype(desc)
+    if workspace is None or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    _check(lib().bass_append_verify_attention(
+        ctypes.byref(desc), _dev(Q, "Q", et, qshape), _dev(K_new, "K_new", et, rows), _dev(V_new, "V_new", et, rows),
+        _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+        _dev(ctx_len, "ctx_len", torch.int32, (desc.B,)), _dev(draft_len, "draft_len", torch.int32, (desc.B,)),
+        _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
+        ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_append_verify_attention")
 
 
 def bass_spec_accept(p, q, draft_tok, n_draft, u, n_accept, next_token, ctx_len=None, dev_status=None, stream=None):

@@ -22,82 +22,78 @@ struct KvParams {
   int32_t* status;
 };
 
-// One workgroup per (row slot i, sequence b); threads sweep (kv head, 8-element chunk).
+// One thread per (sequence b, row slot i, kv head, 16-byte chunk of the row): everything a thread
+// needs is two length words and one 16-byte load per tensor, so the whole launch is one short
+// dependent chain (lengths -> row loads -> stores) however few rows there are.
+// Cache token of row slot i of sequence b; false if the slot is unused or falls outside the
+// cache.  The thread that handles the first chunk of the row (report = true) raises the status bit
+// for a row count outside [0, kmax] (once, from slot 0) and for a used row outside the cache.
+__device__ inline bool row_target(const KvParams& p, int b, int i, bool report, long& tok) {
+  int n = p.cnt[b];
+  bool bad = false;
+  if (n < 0) { n = 0; bad = (i == 0); }
+  if (n > p.kmax) { n = p.kmax; bad = (i == 0); }
+  tok = (long)p.off[b] + i;
+  const bool active = i < n;
+  const bool inside = tok >= 0 && tok < p.Lcap;
+  if (active && !inside) bad = true;
+  if (bad && report && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
+  return active && inside;
+}
+
 template <bool kGather>
 __global__ __launch_bounds__(256) void kv_rows_bf16(KvParams p) {
-  const int b = blockIdx.y, i = blockIdx.x;
-  int n = p.cnt[b];
-  const int off = p.off[b];
-  bool bad = false;
-  if (n < 0) { n = 0; bad = true; }
-  if (n > p.kmax) { n = p.kmax; bad = true; }
-  if (i >= n) {
-    if (bad && i == 0 && threadIdx.x == 0 && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-    return;
-  }
-  const long tok = (long)off + i;
-  if (tok < 0 || tok >= p.Lcap) bad = true;
-  if (bad) {
-    if (threadIdx.x == 0 && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-    if (tok < 0 || tok >= p.Lcap) return;
-  }
-  const int blk = (int)(tok / kBlockTokens), w = (int)(tok % kBlockTokens);
   const int chunks = p.D / 8;
-  const size_t blk_elems = (size_t)kBlockTokens * p.D;
-  for (int item = threadIdx.x; item < p.Hkv * chunks; item += blockDim.x) {
-    const int kvh = item / chunks, d0 = (item % chunks) * 8;
-    const size_t row = (((size_t)b * p.kmax + i) * p.Hkv + kvh) * p.D + d0;
-    const size_t base = (((size_t)b * p.Hkv + kvh) * p.nblk + blk) * blk_elems;
-    uint16_t* kc = (uint16_t*)p.Kc + base;
-    uint16_t* vc = (uint16_t*)p.Vc + base;
-    if (!kGather) {
-      const uint4 kv = *(const uint4*)((const uint16_t*)p.Kr + row);
-      *(uint4*)(kc + k_elem_offset(p.D, w, d0)) = kv;  // 8 consecutive d share one 16-byte slot
-      const uint4 vv = *(const uint4*)((const uint16_t*)p.Vr + row);
-      const uint16_t* ve = (const uint16_t*)&vv;
+  const long item = (long)blockIdx.x * 256 + threadIdx.x;  // over [B][kmax][Hkv][chunks]
+  if (item >= (long)p.B * p.kmax * p.Hkv * chunks) return;
+  const int ck = (int)(item % chunks);
+  const int kvh = (int)((item / chunks) % p.Hkv);
+  const int i = (int)((item / ((long)chunks * p.Hkv)) % p.kmax);
+  const int b = (int)(item / ((long)chunks * p.Hkv * p.kmax));
+  long tok;
+  if (!row_target(p, b, i, ck == 0 && kvh == 0, tok)) return;
+  const int blk = (int)(tok / kBlockTokens), w = (int)(tok % kBlockTokens);
+  const int d0 = ck * 8;
+  const size_t row = (size_t)item * 8;  // [B][kmax][Hkv][D] element offset of this chunk
+  const size_t base = (((size_t)b * p.Hkv + kvh) * p.nblk + blk) * ((size_t)kBlockTokens * p.D);
+  uint16_t* kc = (uint16_t*)p.Kc + base;
+  uint16_t* vc = (uint16_t*)p.Vc + base;
+  if (!kGather) {
+    const uint4 kv = *(const uint4*)((const uint16_t*)p.Kr + row);
+    const uint4 vv = *(const uint4*)((const uint16_t*)p.Vr + row);
+    *(uint4*)(kc + k_elem_offset(p.D, w, d0)) = kv;  // 8 consecutive d share one 16-byte slot
+    const uint16_t* ve = (const uint16_t*)&vv;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) vc[v_elem_offset(p.D, w, d0 + e)] = ve[e];
-    } else {
-      *(uint4*)((uint16_t*)p.Kr + row) = *(const uint4*)(kc + k_elem_offset(p.D, w, d0));
-      uint4 vv;
-      uint16_t* ve = (uint16_t*)&vv;
+    for (int e = 0; e < 8; ++e) vc[v_elem_offset(p.D, w, d0 + e)] = ve[e];
+  } else {
+    *(uint4*)((uint16_t*)p.Kr + row) = *(const uint4*)(kc + k_elem_offset(p.D, w, d0));
+    uint4 vv;
+    uint16_t* ve = (uint16_t*)&vv;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ve[e] = vc[v_elem_offset(p.D, w, d0 + e)];
-      *(uint4*)((uint16_t*)p.Vr + row) = vv;
-    }
+    for (int e = 0; e < 8; ++e) ve[e] = vc[v_elem_offset(p.D, w, d0 + e)];
+    *(uint4*)((uint16_t*)p.Vr + row) = vv;
   }
 }
 
 template <bool kGather>
 __global__ __launch_bounds__(256) void kv_rows_fp32(KvParams p) {
-  const int b = blockIdx.y, i = blockIdx.x;
-  int n = p.cnt[b];
-  const int off = p.off[b];
-  bool bad = false;
-  if (n < 0) { n = 0; bad = true; }
-  if (n > p.kmax) { n = p.kmax; bad = true; }
-  if (i >= n) {
-    if (bad && i == 0 && threadIdx.x == 0 && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-    return;
-  }
-  const long tok = (long)off + i;
-  if (tok < 0 || tok >= p.Lcap) bad = true;
-  if (bad) {
-    if (threadIdx.x == 0 && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-    if (tok < 0 || tok >= p.Lcap) return;
-  }
   const int chunks = p.D / 4;
-  for (int item = threadIdx.x; item < p.Hkv * chunks; item += blockDim.x) {
-    const int kvh = item / chunks, d0 = (item % chunks) * 4;
-    const size_t row = (((size_t)b * p.kmax + i) * p.Hkv + kvh) * p.D + d0;
-    const size_t dst = (((size_t)b * p.Hkv + kvh) * p.Lcap + tok) * p.D + d0;
-    if (!kGather) {
-      *(float4*)((float*)p.Kc + dst) = *(const float4*)((const float*)p.Kr + row);
-      *(float4*)((float*)p.Vc + dst) = *(const float4*)((const float*)p.Vr + row);
-    } else {
-      *(float4*)((float*)p.Kr + row) = *(const float4*)((const float*)p.Kc + dst);
-      *(float4*)((float*)p.Vr + row) = *(const float4*)((const float*)p.Vc + dst);
-    }
+  const long item = (long)blockIdx.x * 256 + threadIdx.x;  // over [B][kmax][Hkv][chunks]
+  if (item >= (long)p.B * p.kmax * p.Hkv * chunks) return;
+  const int ck = (int)(item % chunks);
+  const int kvh = (int)((item / chunks) % p.Hkv);
+  const int i = (int)((item / ((long)chunks * p.Hkv)) % p.kmax);
+  const int b = (int)(item / ((long)chunks * p.Hkv * p.kmax));
+  long tok;
+  if (!row_target(p, b, i, ck == 0 && kvh == 0, tok)) return;
+  const size_t row = (size_t)item * 4;
+  const size_t dst = (((size_t)b * p.Hkv + kvh) * p.Lcap + tok) * p.D + ck * 4;
+  if (!kGather) {
+    *(float4*)((float*)p.Kc + dst) = *(const float4*)((const float*)p.Kr + row);
+    *(float4*)((float*)p.Vc + dst) = *(const float4*)((const float*)p.Vr + row);
+  } else {
+    *(float4*)((float*)p.Kr + row) = *(const float4*)((const float*)p.Kc + dst);
+    *(float4*)((float*)p.Vr + row) = *(const float4*)((const float*)p.Vc + dst);
   }
 }
 
@@ -107,9 +103,11 @@ static int launch_rows(const bass_attn_desc* d, void* Kc, void* Vc, void* Kr, vo
   int rc = check_desc(d);
   if (rc != BASS_OK) return rc;
   if (!Kc || !Vc || !Kr || !Vr || !off || !cnt) return BASS_ERR_INVALID_ARG;
-  if (d->B > 65535) return BASS_ERR_UNSUPPORTED;
+  const int chunk = d->dtype == BASS_DTYPE_BF16 ? 8 : 4;
+  const int64_t items = (int64_t)d->B * d->kmax * d->Hkv * (d->D / chunk);
+  if ((items + 255) / 256 > 0x7fffffff) return BASS_ERR_UNSUPPORTED;
   KvParams p{d->B, d->kmax, d->Hkv, d->D, d->Lcap, num_blocks(d->Lcap), Kc, Vc, Kr, Vr, off, cnt, status};
-  dim3 grid((unsigned)d->kmax, (unsigned)d->B);
+  dim3 grid((unsigned)((items + 255) / 256));
   hipStream_t s = (hipStream_t)stream;
   if (d->dtype == BASS_DTYPE_BF16)
     hipLaunchKernelGGL(kv_rows_bf16<kGather>, grid, dim3(256), 0, s, p);

@@ -32,6 +32,7 @@ namespace bass {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 static int g_attention_waves = 0;  // 0 = default
 #ifdef BASS_EXP_TRACE
@@ -54,6 +55,8 @@ struct AttnParams {
   const void* Q;
   const void* Kc;
   const void* Vc;
+  const void* Knew;  // [B,kmax,Hkv,D] rows of this step to append first, or null
+  const void* Vnew;
   const int32_t* ctx_len;
   const int32_t* draft_len;
   float* O;
@@ -158,7 +161,6 @@ __device__ inline void store_dev(float* dst, float a, float b) {
 
 // 128-bit variants through raw buffer accesses with the device-scope cache policy (sc1); the
 // buffer descriptor also bounds the access: offsets beyond `bytes` read zero / are dropped.
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 constexpr int kAuxDeviceScope = 16;  // sc1
 
 // base and bytes are wave-uniform by construction; saying so keeps the descriptor in scalar
@@ -550,6 +552,75 @@ __device__ inline void block_dispatch(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 3
     block_step<D, NT, true>(r, qf, st, tok0, n_valid, lim, scale_log2, lane);
 }
 
+// Fused append (optional).  The rows of this step's own tokens are copied into the cache by the
+// wavefront whose share of blocks holds them, before it starts streaming: every cache line is
+// then written and read by the same wavefront (store, wait for the acknowledgement, load), and
+// no other wavefront reads those blocks in this launch.  Returns whether anything was written.
+template <int D>
+__device__ inline bool append_own_rows_bf16(const AttnParams& p, const Unit& u, int blk_lo, int nblk, int lane) {
+  const int t_lo = max(u.L, blk_lo * kBlockTokens);
+  const int t_hi = min(u.L + u.nq, (blk_lo + nblk) * kBlockTokens);
+  if (t_lo >= t_hi) return false;
+  uint16_t* kc = (uint16_t*)const_cast<void*>(p.Kc);
+  uint16_t* vc = (uint16_t*)const_cast<void*>(p.Vc);
+  const uint16_t* kn = (const uint16_t*)p.Knew + (((size_t)u.b * p.kmax) * p.Hkv + u.kvh) * D;
+  const uint16_t* vn = (const uint16_t*)p.Vnew + (((size_t)u.b * p.kmax) * p.Hkv + u.kvh) * D;
+  const size_t row_stride = (size_t)p.Hkv * D;  // between consecutive rows of one (sequence, kv head)
+  const size_t unit_base = ((size_t)u.b * p.Hkv + u.kvh) * p.nblk_cap * ((size_t)kBlockTokens * D);
+  auto cache_off = [&](int t) { return unit_base + (size_t)(t / kBlockTokens) * ((size_t)kBlockTokens * D); };
+  constexpr int kLanesPerRow = D / 8, kRowsPerPass = 64 / kLanesPerRow, kPasses = 8 / kRowsPerPass;
+  // Eight tokens per round; all loads of a round are issued before its first store.  Loads are
+  // unconditional (a row index past the end is clamped to the last row) and only the stores are
+  // guarded, so that the staging values stay in registers.
+  for (int t0 = t_lo; t0 < t_hi; t0 += 8) {
+    u32x4 kv[kPasses];
+    unsigned vv[8][D / 64];
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) {  // K: a lane copies one 16-byte chunk of one row
+      const int t = min(t0 + ps * kRowsPerPass + lane / kLanesPerRow, t_hi - 1);
+      kv[ps] = *(const u32x4*)(kn + (size_t)(t - u.L) * row_stride + 8 * (lane % kLanesPerRow));
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {  // V: a lane copies elements lane, lane + 64 of every row
+      const int t = min(t0 + j, t_hi - 1);
+#pragma unroll
+      for (int h = 0; h < D / 64; ++h) vv[j][h] = vn[(size_t)(t - u.L) * row_stride + lane + 64 * h];
+    }
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) {
+      const int t = t0 + ps * kRowsPerPass + lane / kLanesPerRow;
+      if (t < t_hi) *(u32x4*)(kc + cache_off(t) + k_elem_offset(D, t % kBlockTokens, 8 * (lane % kLanesPerRow))) = kv[ps];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int t = t0 + j;
+      if (t < t_hi) {
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+          vc[cache_off(t) + v_elem_offset(D, t % kBlockTokens, lane + 64 * h)] = (uint16_t)vv[j][h];
+      }
+    }
+  }
+  return true;
+}
+
+__device__ inline bool append_own_rows_fp32(const AttnParams& p, const Unit& u, int blk_lo, int nblk, int lane) {
+  const int t_lo = max(u.L, blk_lo * kBlockTokens);
+  const int t_hi = min(u.L + u.nq, (blk_lo + nblk) * kBlockTokens);
+  if (t_lo >= t_hi) return false;
+  float* kc = (float*)const_cast<void*>(p.Kc);
+  float* vc = (float*)const_cast<void*>(p.Vc);
+  for (int t = t_lo; t < t_hi; ++t) {
+    const size_t row = (((size_t)u.b * p.kmax + (t - u.L)) * p.Hkv + u.kvh) * p.D;
+    const size_t dst = (((size_t)u.b * p.Hkv + u.kvh) * p.Lcap + t) * p.D;
+    for (int d = 4 * lane; d < p.D; d += 256) {
+      *(float4*)(kc + dst + d) = *(const float4*)((const float*)p.Knew + row + d);
+      *(float4*)(vc + dst + d) = *(const float4*)((const float*)p.Vnew + row + d);
+    }
+  }
+  return true;
+}
+
 template <int D, int NT>
 struct QFrag {
   bf16x8 q[NT][D / 32];  // B operand: lane (col, grp) holds query row 16 nt + col, elements 32 t + 8 grp .. +7
@@ -647,6 +718,11 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     QFrag<D, NT> qc, qB;
     load_queries<D, NT>(p, uA, true, col, grp, qc);
     if constexpr (kPair) load_queries<D, NT>(p, uB, hasB, col, grp, qB);
+    if (p.Knew) {
+      bool wrote = append_own_rows_bf16<D>(p, uA, x - uA.begin, nA, lane);
+      if (hasB) wrote |= append_own_rows_bf16<D>(p, uB, 0, nB, lane);
+      if (wrote) partial_stores_done();  // acknowledged before the same lines are fetched below
+    }
 
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
@@ -760,6 +836,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
     const int n_valid = u.L + u.nq;
     const int tok_lo = blk0 * kBlockTokens;
     const int tok_hi = min(n_valid, (blk0 + nseg) * kBlockTokens);
+    if (p.Knew && append_own_rows_fp32(p, u, blk0, nseg, lane)) partial_stores_done();
     const float* kbase = (const float*)p.Kc + ((size_t)u.b * p.Hkv + u.kvh) * p.Lcap * D;
     const float* vbase = (const float*)p.Vc + ((size_t)u.b * p.Hkv + u.kvh) * p.Lcap * D;
     const size_t slot = (size_t)w + (size_t)u.b * p.Hkv + u.kvh;
@@ -876,13 +953,16 @@ extern "C" size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* d)
   return bass::workspace_bytes(d);
 }
 
-extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, const void* Kcache, const void* Vcache,
-                                     const int32_t* ctx_len, const int32_t* draft_len, float* O, float* lse,
-                                     void* workspace, size_t workspace_bytes, int32_t* dev_status, void* stream) {
-  using namespace bass;
+namespace bass {
+
+static int launch_attention(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
+                            const void* Kcache, const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                            float* O, float* lse, void* workspace, size_t workspace_bytes, int32_t* dev_status,
+                            void* stream) {
   int rc = check_desc(d);
   if (rc != BASS_OK) return rc;
   if (!Q || !Kcache || !Vcache || !ctx_len || !draft_len || !O || !workspace) return BASS_ERR_INVALID_ARG;
+  if ((K_new == nullptr) != (V_new == nullptr)) return BASS_ERR_INVALID_ARG;
   if (((uintptr_t)workspace & 15) != 0) return BASS_ERR_INVALID_ARG;
   const int g = d->Hq / d->Hkv;
   const int rows_max = d->kmax * g;
@@ -895,7 +975,8 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves();
   p.scale_log2 = d->scale * 1.4426950408889634f;
-  p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.ctx_len = ctx_len; p.draft_len = draft_len;
+  p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.Knew = K_new; p.Vnew = V_new;
+  p.ctx_len = ctx_len; p.draft_len = draft_len;
   p.O = O; p.lse = lse; p.status = dev_status;
 #ifdef BASS_EXP_TRACE
   p.trace = g_trace;
@@ -922,4 +1003,22 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
 #undef BASS_LAUNCH
   }
   return launch_status();
+}
+
+}  // namespace bass
+
+extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, const void* Kcache, const void* Vcache,
+                                     const int32_t* ctx_len, const int32_t* draft_len, float* O, float* lse,
+                                     void* workspace, size_t workspace_bytes, int32_t* dev_status, void* stream) {
+  return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                workspace_bytes, dev_status, stream);
+}
+
+extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void* Q, const void* K_new,
+                                            const void* V_new, void* Kcache, void* Vcache, const int32_t* ctx_len,
+                                            const int32_t* draft_len, float* O, float* lse, void* workspace,
+                                            size_t workspace_bytes, int32_t* dev_status, void* stream) {
+  if (!K_new || !V_new) return BASS_ERR_INVALID_ARG;
+  return bass::launch_attention(d, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                workspace_bytes, dev_status, stream);
 }

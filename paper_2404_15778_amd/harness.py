@@ -8,8 +8,8 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (AttnDesc, alloc_kv_cache, alloc_workspace, bass_kv_append, bass_kv_gather, bass_spec_accept,
-               bass_verify_attention, make_desc)
+from . import (AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
+               bass_spec_accept, bass_verify_attention, make_desc)
 
 
 def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
@@ -58,14 +58,21 @@ class DeviceAttention:
                               self.lse if want_lse else None, self.ws, self.status)
         return self.O, self.lse
 
+    def append_verify(self, Q, K_new, V_new, ctx_len, draft_len, want_lse=True):
+        """Append this step's rows and verify in one launch."""
+        bass_append_verify_attention(self.desc, Q, K_new, V_new, self.Kc, self.Vc, ctx_len, draft_len, self.O,
+                                     self.lse if want_lse else None, self.ws, self.status)
+        return self.O, self.lse
+
 
 def i32(a, device="cuda"):
     return torch.as_tensor(np.asarray(a, dtype=np.int32), device=device)
 
 
-def run_attention_workload(w, poison=True, device="cuda"):
+def run_attention_workload(w, poison=True, device="cuda", fused=False):
     """Whole attention path on a synthetic workload (see workloads.AttnWorkload): fill the cache
-    with the context rows, append the step's own rows, verify.  Returns (O, lse, status) on host."""
+    with the context rows, append the step's own rows, verify (two launches, or one with
+    fused=True).  Returns (O, lse, status, DeviceAttention) with O, lse on the host."""
     da = DeviceAttention(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, w.dtype, w.scale, device, poison)
     K, V = to_device(w.K, device), to_device(w.V, device)
     ctx, nq = i32(w.ctx_len, device), i32(w.draft_len, device)
@@ -78,8 +85,11 @@ def run_attention_workload(w, poison=True, device="cuda"):
         L, n = int(w.ctx_len[b]), int(w.draft_len[b])
         Kn[b, :n] = w.K[b, L:L + n]
         Vn[b, :n] = w.V[b, L:L + n]
-    da.append(to_device(Kn, device), to_device(Vn, device), ctx, nq)
-    O, lse = da.verify(to_device(w.Q, device), ctx, nq)
+    if fused:
+        O, lse = da.append_verify(to_device(w.Q, device), to_device(Kn, device), to_device(Vn, device), ctx, nq)
+    else:
+        da.append(to_device(Kn, device), to_device(Vn, device), ctx, nq)
+        O, lse = da.verify(to_device(w.Q, device), ctx, nq)
     torch.cuda.synchronize()
     return to_host(O), to_host(lse), int(da.status.item()), da
 

@@ -23,12 +23,12 @@ def hip():
     return harness
 
 
-def check_against_oracle(hip, w, waves=None):
+def check_against_oracle(hip, w, waves=None, fused=False):
     import paper_2404_15778_amd as bass
     if waves is not None:
         bass.bass_set_attention_waves(waves)
     try:
-        O, lse, status, _ = hip.run_attention_workload(w, poison=True)
+        O, lse, status, _ = hip.run_attention_workload(w, poison=True, fused=fused)
     finally:
         bass.bass_set_attention_waves(0)
     Or, lser = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
@@ -97,3 +97,54 @@ def test_kv_append_then_gather_is_bit_exact(hip):
             np.testing.assert_array_equal(K[b, :t], w.K[b, :t])
             np.testing.assert_array_equal(V[b, :t], w.V[b, :t])
         assert status == 0
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+@pytest.mark.parametrize("waves", [64, 1024])
+def test_fused_append_verify_equals_separate_calls(hip, dtype, D, waves):
+    import torch
+    import paper_2404_15778_amd as bass
+    # step rows straddle 32-token block boundaries (ctx 30, 63) and wavefront share boundaries
+    w = wl.make_attention("fused", 5, 8, 4, D, dtype, [30, 63, 0, 500, 129], [6, 3, 2, 5, 0], 9, kmax=6, Lcap=520)
+    check_against_oracle(hip, w, waves=waves, fused=True)
+    bass.bass_set_attention_waves(waves)
+    try:
+        O1, lse1, st1, da1 = hip.run_attention_workload(w, poison=True, fused=False)
+        O2, lse2, st2, da2 = hip.run_attention_workload(w, poison=True, fused=True)
+    finally:
+        bass.bass_set_attention_waves(0)
+    np.testing.assert_array_equal(O1, O2)
+    np.testing.assert_array_equal(lse1, lse2)
+    assert st1 == 0 and st2 == 0
+    total = w.ctx_len + w.draft_len
+    n = int(total.max())
+    for da in (da1, da2):
+        K, V = da.gather(hip.i32(np.zeros(w.B)), hip.i32(total), n)
+        torch.cuda.synchronize()
+        K, V = hip.to_host(K), hip.to_host(V)
+        for b in range(w.B):
+            t = int(total[b])
+            np.testing.assert_array_equal(K[b, :t], w.K[b, :t])
+            np.testing.assert_array_equal(V[b, :t], w.V[b, :t])
+
+
+def test_repeated_calls_share_one_workspace(hip):
+    # the arrival counters must be left clean by every call: same workspace, different shapes / spreads
+    import torch
+    import paper_2404_15778_amd as bass
+    w = wl.make_attention("rep", 4, 4, 4, 128, "bf16", [700, 90, 333, 1500], [3, 6, 1, 4], 11, kmax=6, Lcap=1600)
+    Or, _ = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    _, _, _, da = hip.run_attention_workload(w, poison=True)
+    Q = hip.to_device(w.Q)
+    ctx, nq = hip.i32(w.ctx_len), hip.i32(w.draft_len)
+    try:
+        for waves in (64, 1024, 200, 8192, 64):
+            bass.bass_set_attention_waves(waves)
+            for _ in range(3):
+                da.O.fill_(float("nan"))
+                O, _ = da.verify(Q, ctx, nq)
+                torch.cuda.synchronize()
+                assert np.abs(hip.to_host(O) - Or).max() <= TOL["bf16"]
+    finally:
+        bass.bass_set_attention_waves(0)
+    assert int(da.status.item()) == 0
