@@ -718,12 +718,6 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     QFrag<D, NT> qc, qB;
     load_queries<D, NT>(p, uA, true, col, grp, qc);
     if constexpr (kPair) load_queries<D, NT>(p, uB, hasB, col, grp, qB);
-    if (p.Knew) {
-      bool wrote = append_own_rows_bf16<D>(p, uA, x - uA.begin, nA, lane);
-      if (hasB) wrote |= append_own_rows_bf16<D>(p, uB, 0, nB, lane);
-      if (wrote) partial_stores_done();  // acknowledged before the same lines are fetched below
-    }
-
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
     int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
@@ -763,11 +757,28 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane);
 #endif
     };
+    // Fused append: this share's own new rows go into the cache before the blocks that hold them
+    // are fetched.  They sit at the end of a unit, so normally the first fetches can be issued
+    // first and the store acknowledgements are awaited while those fetches are in flight.
+    constexpr int kPrefetched = (NT <= 2) ? 2 : 1;  // blocks fetched before the loop starts
+    constexpr int kNoNewRows = 1 << 30;
+    int first_new = kNoNewRows;                      // first step whose block holds a new row
+    if (p.Knew) {
+      if (uA.L / kBlockTokens < (x - uA.begin) + nA) first_new = max(uA.L / kBlockTokens - (x - uA.begin), 0);
+      else if (hasB && uB.L / kBlockTokens < nB) first_new = nA + uB.L / kBlockTokens;
+    }
+    auto append_rows = [&]() {
+      bool wrote = append_own_rows_bf16<D>(p, uA, x - uA.begin, nA, lane);
+      if (hasB) wrote |= append_own_rows_bf16<D>(p, uB, 0, nB, lane);
+      if (wrote) partial_stores_done();  // acknowledged before the same lines are fetched
+    };
+    if (first_new < kPrefetched) append_rows();  // (never without K_new: first_new stays kNoNewRows)
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
       KvRegs<D> r0, r1, r2;
       fetch(r0, 0);
       fetch(r1, 1);
+      if (first_new >= kPrefetched && first_new != kNoNewRows) append_rows();
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
@@ -780,6 +791,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       // many query rows need the registers for accumulators: two-deep ring
       KvRegs<D> r0, r1;
       fetch(r0, 0);
+      if (first_new >= kPrefetched && first_new != kNoNewRows) append_rows();
       for (int s = 0; s < n; s += 2) {
         fetch(r1, s + 1);
         step(r0, s);
