@@ -1,0 +1,118 @@
+"""GPU edge cases of the attention path: degenerate batches, exact-fit caches, clamped lengths,
+more sequences than a wavefront has lanes, the largest query-row count."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "fp32": 1e-5}
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2404_15778_amd import harness
+    return harness
+
+
+def check(hip, w, fused=False):
+    O, lse, status, da = hip.run_attention_workload(w, poison=True, fused=fused)
+    Or, lser = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    assert status == 0 and np.isfinite(O).all()
+    assert np.abs(O - Or).max() <= TOL[w.dtype]
+    assert np.abs(lse - lser).max() <= TOL[w.dtype]
+    return O, da
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_all_sequences_inactive_gives_zeros(hip, dtype):
+    w = wl.make_attention("inactive", 3, 4, 2, 64, dtype, [10, 0, 40], [0, 0, 0], 0, kmax=3, Lcap=64)
+    O, lse, status, _ = hip.run_attention_workload(w, poison=True)
+    assert status == 0 and (O == 0).all() and (lse == 0).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_single_sequence_and_empty_contexts(hip, dtype, fused):
+    check(hip, wl.make_attention("one", 1, 2, 2, 64, dtype, [0], [1], 1, kmax=1, Lcap=1), fused)
+    check(hip, wl.make_attention("empty_ctx", 4, 4, 4, 64, dtype, [0, 0, 0, 0], [4, 1, 2, 3], 2, kmax=4, Lcap=40), fused)
+
+
+@pytest.mark.parametrize("ctx", [31, 32, 33, 63, 64, 65])
+def test_lengths_around_block_boundaries(hip, ctx):
+    w = wl.make_attention("edge", 2, 2, 2, 128, "bf16", [ctx, ctx - 1], [1, 2], ctx, kmax=2, Lcap=96)
+    check(hip, w, fused=True)
+
+
+def test_cache_filled_to_capacity(hip):
+    # the last draft row lands on the cache's last token, capacity a multiple of the block size and not
+    for Lcap in (96, 100):
+        w = wl.make_attention("full", 2, 4, 4, 128, "bf16", [Lcap - 4, Lcap - 1], [4, 1], Lcap, kmax=4, Lcap=Lcap)
+        check(hip, w, fused=True)
+
+
+def test_more_sequences_than_lanes(hip):
+    # 70 sequences: the schedule's 64-sequence register chunk is not enough
+    rng = np.random.default_rng(5)
+    ctx = rng.integers(0, 80, size=70)
+    nq = rng.integers(0, 4, size=70)
+    nq[[0, 64, 69]] = [2, 3, 1]
+    for dtype in ("bf16", "fp32"):
+        w = wl.make_attention("b70", 70, 2, 2, 64, dtype, ctx, nq, 6, kmax=3, Lcap=96)
+        check(hip, w, fused=(dtype == "bf16"))
+
+
+def test_largest_row_count_bf16(hip):
+    # kmax * (Hq / Hkv) = 64 query rows per kv head: four 16-row tiles
+    w = wl.make_attention("rows64", 2, 16, 2, 128, "bf16", [100, 37], [8, 5], 7, kmax=8, Lcap=128)
+    check(hip, w)
+    w = wl.make_attention("rows64_d64", 2, 16, 2, 64, "bf16", [100, 37], [8, 5], 7, kmax=8, Lcap=128)
+    check(hip, w, fused=True)
+
+
+def test_lengths_outside_the_cache_are_clamped_and_reported(hip):
+    import torch
+    import paper_2404_15778_amd as bass
+    w = wl.make_attention("clamp", 3, 2, 2, 128, "bf16", [50, 20, 30], [2, 2, 2], 8, kmax=2, Lcap=64)
+    _, _, _, da = hip.run_attention_workload(w, poison=False)
+    Q = hip.to_device(w.Q)
+    bad_ctx = hip.i32([50, 63, -5])    # 63 + 2 > Lcap, negative length
+    bad_nq = hip.i32([2, 2, 7])        # 7 > kmax
+    da.status.zero_()
+    O, _ = da.verify(Q, bad_ctx, bad_nq)
+    torch.cuda.synchronize()
+    assert int(da.status.item()) & bass.STATUS_LEN_CLAMPED
+    assert np.isfinite(hip.to_host(O)).all()
+    # the well-formed sequence is unaffected
+    Or, _ = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    assert np.abs(hip.to_host(O)[0] - Or[0]).max() <= TOL["bf16"]
+    # append outside the cache: rows are dropped and reported
+    da.status.zero_()
+    Kn = torch.zeros((3, 2, 2, 128), dtype=torch.bfloat16, device="cuda")
+    da.append(Kn, Kn, hip.i32([63, 0, 0]), hip.i32([2, 0, 5]))
+    torch.cuda.synchronize()
+    assert int(da.status.item()) & bass.STATUS_LEN_CLAMPED
+
+
+def test_lse_is_optional(hip):
+    import torch
+    w = wl.make_attention("nolse", 2, 4, 4, 128, "bf16", [70, 10], [3, 2], 9, kmax=3, Lcap=80)
+    _, _, _, da = hip.run_attention_workload(w, poison=True)
+    Or, _ = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    O, _ = da.verify(hip.to_device(w.Q), hip.i32(w.ctx_len), hip.i32(w.draft_len), want_lse=False)
+    torch.cuda.synchronize()
+    assert np.abs(hip.to_host(O) - Or).max() <= TOL["bf16"]
+
+
+def test_gqa_equals_mha_with_repeated_kv_heads_on_gpu(hip):
+    w = wl.make_attention("gqa", 2, 8, 2, 128, "bf16", [90, 45], [3, 2], 10, kmax=3, Lcap=100)
+    O, _, _, _ = hip.run_attention_workload(w)
+    m = wl.make_attention("mha", 2, 8, 8, 128, "bf16", [90, 45], [3, 2], 10, kmax=3, Lcap=100)
+    m.Q, m.K, m.V = w.Q, np.repeat(w.K, 4, axis=2), np.repeat(w.V, 4, axis=2)
+    Om, _, _, _ = hip.run_attention_workload(m)
+    # same numbers, different work decomposition: equal up to the split-context rounding
+    assert np.abs(O - Om).max() <= 1e-5

@@ -1,0 +1,61 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py
+times (default work spread, append fused into the attention launch).  The oracle cannot compute
+every output row of these sizes in seconds, so rows are sampled (always including the extremes:
+shortest / longest sequence, first / last query, first / last head) and checked one by one;
+plus properties that hold at any size."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2  # bf16 inputs
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2404_15778_amd import harness
+    return harness
+
+
+def sample_rows(w, rng, n):
+    rows = set()
+    order = np.argsort(w.ctx_len)
+    for b in (int(order[0]), int(order[-1])):
+        for i in (0, int(w.draft_len[b]) - 1):
+            for h in (0, w.Hq - 1):
+                rows.add((b, i, h))
+    while len(rows) < n:
+        b = int(rng.integers(w.B))
+        rows.add((b, int(rng.integers(w.draft_len[b])), int(rng.integers(w.Hq))))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("make,nsample", [(wl.config2, 48), (wl.config4, 48), (wl.config3, 40)])
+def test_full_size_sampled_rows(hip, make, nsample):
+    w = make(0)
+    print(f"{w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} D={w.D} kv_bytes={w.kv_bytes}", flush=True)
+    O, lse, status, da = hip.run_attention_workload(w, poison=True, fused=True)
+    assert status == 0
+    assert np.isfinite(O).all() and np.isfinite(lse).all()
+    for b in range(w.B):
+        assert (O[b, int(w.draft_len[b]):] == 0).all() and (lse[b, int(w.draft_len[b]):] == 0).all()
+    worst = 0.0
+    for (b, i, h) in sample_rows(w, np.random.default_rng(1), nsample):
+        ref, lref = oracle.verify_attention_row(w.Q, w.K, w.V, b, i, h, int(w.ctx_len[b]), w.scale)
+        err = float(np.abs(O[b, i, h] - ref).max())
+        worst = max(worst, err)
+        assert err <= TOL, (b, i, h, err)
+        assert abs(float(lse[b, i, h]) - lref) <= TOL, (b, i, h)
+    print(f"{w.name}: worst sampled max-abs error {worst:.3e}", flush=True)
+    # a second launch on the same caches (rows already appended) reproduces the result bit for bit
+    import torch
+    Q, ctx, nq = hip.to_device(w.Q), hip.i32(w.ctx_len), hip.i32(w.draft_len)
+    O2, lse2 = da.verify(Q, ctx, nq)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(hip.to_host(O2), O)
+    np.testing.assert_array_equal(hip.to_host(lse2), lse)
