@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--waves", type=int, default=0, help="override the attention work spread (0 = library default)")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     ap.add_argument("--separate-append", action="store_true", help="bass_kv_append + bass_verify_attention as two launches")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run four 1 GiB device-to-device copies (a kernel of known traffic for counter scaling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -141,6 +143,14 @@ def main():
             assert torch.equal(O, O_ref) and torch.equal(n_accept, nacc_ref) and torch.equal(next_token, tok_ref), \
                 "graph replay differs from eager execution"
         run_step = graph.replay
+
+    if args.calibration_copy:  # 1 GiB read + 1 GiB written per copy, by a plain elementwise copy kernel
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         run_step()
