@@ -127,9 +127,10 @@ int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void*
  * The two calls above in ONE launch: appends rows i < draft_len[b] of K_new, V_new
  * [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
  * bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, ...) would, and computes
- * bass_verify_attention over the updated caches.  Results (O, lse, cache contents) are identical
- * to the two separate calls.  Rows of sequences whose lengths had to be clamped are appended at
- * the clamped positions.  Arguments as in those calls.
+ * bass_verify_attention over the updated caches.  The cache contents are identical to those after
+ * the two separate calls; O and lse agree with them up to rounding (the fused launch cuts the
+ * context at other points).  Rows of sequences whose lengths had to be clamped are appended at the
+ * clamped positions.  Arguments as in those calls.
  */
 int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, const void* K_new,
                                  const void* V_new, void* Kcache, void* Vcache,

@@ -35,6 +35,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 static int g_attention_waves = 0;  // 0 = default
+static int g_append_pad = 2;      // virtual blocks per unit when the append is fused (measured best: 2)
 #ifdef BASS_EXP_TRACE
 static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
@@ -51,6 +52,7 @@ static int attention_waves() {
 
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
+  int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
   float scale_log2;  // scale * log2(e): scores are kept in the log2 domain
   const void* Q;
   const void* Kc;
@@ -82,6 +84,12 @@ __device__ inline int wave_incl_scan(int v, int lane) {
   return v;
 }
 
+// Length of a unit in the flattened list = its real blocks plus p.pad virtual ones at its end.
+// A virtual block is no work; it stands for the fixed cost of the wavefront that handles the
+// unit's last blocks (with the fused append: copying the step's rows into the cache first), so
+// that this wavefront is handed correspondingly fewer real blocks and finishes with the others.
+__device__ inline int padded_blocks(const AttnParams& p, int nblk) { return nblk > 0 ? nblk + p.pad : 0; }
+
 __device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bool& bad) {
   L = p.ctx_len[b];
   nq = p.draft_len[b];
@@ -90,12 +98,13 @@ __device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bo
 }
 
 struct Unit {
-  int b, kvh, L, nq, nblk;
-  int begin;  // flattened index of the unit's first block
+  int b, kvh, L, nq;
+  int nblk;   // real blocks
+  int begin;  // flattened index of the unit's first block (units are padded_blocks() apart)
 };
 
-// The schedule of a call, held in registers: lane b keeps sequence b's lengths, block count and
-// inclusive block prefix (first 64 sequences; later ones are re-read when needed).
+// The schedule of a call, held in registers: lane b keeps sequence b's lengths, padded block count
+// and inclusive prefix of it (first 64 sequences; later ones are re-read when needed).
 struct Sched {
   int L, nq, nb, inc;
   int total;  // sum over ALL sequences of blocks per kv head (wave-uniform)
@@ -104,14 +113,14 @@ struct Sched {
 __device__ inline Sched make_sched(const AttnParams& p, int lane, bool report) {
   Sched s{0, 0, 0, 0, 0};
   bool any_bad = false;
-  if (lane < p.B) s.nb = seq_blocks(p, lane, s.L, s.nq, any_bad);
+  if (lane < p.B) s.nb = padded_blocks(p, seq_blocks(p, lane, s.L, s.nq, any_bad));
   s.inc = wave_incl_scan(s.nb, lane);
   s.total = __builtin_amdgcn_readlane(s.inc, 63);
   for (int c0 = 64; c0 < p.B; c0 += 64) {
     const int b = c0 + lane;
     int L, nq, nb = 0;
     bool bad = false;
-    if (b < p.B) nb = seq_blocks(p, b, L, nq, bad);
+    if (b < p.B) nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
     any_bad |= bad;
     s.total += __builtin_amdgcn_readlane(wave_incl_scan(nb, lane), 63);
   }
@@ -130,10 +139,11 @@ __device__ inline Unit locate(const AttnParams& p, const Sched& s, int x, int la
       u.b = c0 + src;
       u.L = __builtin_amdgcn_readlane(L, src);
       u.nq = __builtin_amdgcn_readlane(nq, src);
-      u.nblk = __builtin_amdgcn_readlane(nb, src);
-      const int pre = __builtin_amdgcn_readlane(inc, src) - u.nblk;
-      u.kvh = (x - pre * p.Hkv) / u.nblk;
-      u.begin = pre * p.Hkv + u.kvh * u.nblk;
+      const int npad = __builtin_amdgcn_readlane(nb, src);
+      u.nblk = npad - p.pad;
+      const int pre = __builtin_amdgcn_readlane(inc, src) - npad;
+      u.kvh = (x - pre * p.Hkv) / npad;
+      u.begin = pre * p.Hkv + u.kvh * npad;
       return u;
     }
     const int running = __builtin_amdgcn_readlane(inc, 63);
@@ -142,7 +152,7 @@ __device__ inline Unit locate(const AttnParams& p, const Sched& s, int x, int la
     const int b = c0 + lane;
     L = nq = nb = 0;
     bool bad;
-    if (b < p.B) nb = seq_blocks(p, b, L, nq, bad);
+    if (b < p.B) nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
     inc = running + wave_incl_scan(nb, lane);
   }
 }
@@ -703,15 +713,21 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 
   while (x < x_end) {
     const Unit uA = locate(p, sched, x, lane);
-    const int nA = min(x_end, uA.begin + uA.nblk) - x;  // blocks of unit A that are ours
+    const int spanA = min(x_end, uA.begin + uA.nblk + p.pad) - x;  // our stretch of unit A, virtual blocks included
+    const int nA = min(spanA, uA.begin + uA.nblk - x);              // real blocks of unit A that are ours
+    if (nA <= 0) {  // only virtual blocks of this unit fall into our share
+      x += spanA;
+      continue;
+    }
     Unit uB = uA;
-    int nB = 0;
+    int nB = 0, spanB = 0;
     bool hasB = false;
     if constexpr (kPair) {
-      if (x + nA < x_end) {
+      if (x + spanA < x_end) {
         hasB = true;
-        uB = locate(p, sched, x + nA, lane);  // starts at its block 0
-        nB = min(x_end, uB.begin + uB.nblk) - (x + nA);
+        uB = locate(p, sched, x + spanA, lane);  // starts at its block 0
+        spanB = min(x_end, uB.begin + uB.nblk + p.pad) - (x + spanA);
+        nB = min(spanB, uB.nblk);
       }
     }
     const int n = nA + nB;
@@ -818,7 +834,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane, w);
 #endif
     BASS_TRACE(6);
-    x += n;
+    x += spanA + spanB;
   }
 }
 
@@ -845,7 +861,12 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
   while (x < x_end) {
     const Unit u = locate(p, sched, x, lane);
     const int blk0 = x - u.begin;
-    const int nseg = min(x_end, u.begin + u.nblk) - x;
+    const int span = min(x_end, u.begin + u.nblk + p.pad) - x;
+    const int nseg = min(span, u.begin + u.nblk - x);
+    if (nseg <= 0) {  // only virtual blocks of this unit fall into our share
+      x += span;
+      continue;
+    }
     const int rows = u.nq * p.g;
     const int n_valid = u.L + u.nq;
     const int tok_lo = blk0 * kBlockTokens;
@@ -936,7 +957,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
     bool last, unused;
     arrive(p, c, lane, job, last, false, job, unused);
     if (last) combine_jobs<4, 0>(p, job, true, job, false, lane);
-    x += nseg;
+    x += span;
   }
 }
 
@@ -955,6 +976,10 @@ static size_t workspace_bytes(const bass_attn_desc* d) {
 
 #ifdef BASS_EXP_TRACE
 extern "C" void bass_debug_set_trace(void* ptr) { bass::g_trace = (long long*)ptr; }
+#endif
+
+#ifdef BASS_EXP_TRACE
+extern "C" void bass_debug_set_pad(int pad) { bass::g_append_pad = pad; }
 #endif
 
 extern "C" int bass_set_attention_waves(int waves) {
@@ -988,6 +1013,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves();
+  p.pad = K_new ? g_append_pad : 0;
   p.scale_log2 = d->scale * 1.4426950408889634f;
   p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.Knew = K_new; p.Vnew = V_new;
   p.ctx_len = ctx_len; p.draft_len = draft_len;

