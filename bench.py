@@ -43,6 +43,19 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic():
+    """HBM bytes per attention launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE
+    and WRITE_SIZE, each scaled by a 1 GiB copy); None if that summary is not there."""
+    path = os.path.join(ROOT, "profiles", "verify_attn_bf16_cfg2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -104,22 +117,22 @@ def main():
     torch.cuda.synchronize()
 
     def step(events=None):
-        for li, l in enumerate(layers):
-            if events is not None:
-                events[li][0].record()
+        # events (second pass only): [0] before the first attention launch, [1] after the last one,
+        # [2] after the acceptance launch -- all on the stream the kernels are launched on
+        if events is not None:
+            events[0].record()
+        for l in layers:
             if args.separate_append:
                 bass.bass_kv_append(desc, l["Kc"], l["Vc"], l["Kn"], l["Vn"], ctx, nq, status)
                 bass.bass_verify_attention(desc, l["Q"], l["Kc"], l["Vc"], ctx, nq, O, None, ws, status)
             else:  # append of the step's K/V rows fused into the attention launch
                 bass.bass_append_verify_attention(desc, l["Q"], l["Kn"], l["Vn"], l["Kc"], l["Vc"], ctx, nq, O, None,
                                                   ws, status)
-            if events is not None:
-                events[li][1].record()
         if events is not None:
-            events[NL][0].record()
+            events[1].record()
         bass.bass_spec_accept(p, q, tok, ndr, u, n_accept, next_token, ctx_scratch, status)
         if events is not None:
-            events[NL][1].record()
+            events[2].record()
 
     # One step is 2 * layers + 1 launches of 3-40 us each; a serving loop replays them as a HIP graph so
     # that the CPU's launch cost does not pace the GPU.  (The library itself records no memset nodes.)
@@ -163,14 +176,16 @@ def main():
     assert int(status.item()) == 0, "device status word is not clean"
     ms_per_step = 1e3 * wall / args.steps
 
-    # ---- second pass with HIP events around the attention and acceptance launches -------------
+    # ---- second pass: HIP events around the step's run of attention launches and the acceptance ---
+    # (eager launches on the current stream; the NL attention kernels run back to back, so
+    # elapsed / NL is the average duration of one launch including the hand-over to the next)
     attn_ms, accept_ms = [], []
     for _ in range(args.steps):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(NL + 1)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         step(ev)
         torch.cuda.synchronize()
-        attn_ms += [a.elapsed_time(b) for a, b in ev[:NL]]
-        accept_ms.append(ev[NL][0].elapsed_time(ev[NL][1]))
+        attn_ms.append(ev[0].elapsed_time(ev[1]) / NL)
+        accept_ms.append(ev[1].elapsed_time(ev[2]))
     attn_us = 1e3 * float(np.mean(attn_ms))
     accept_us = 1e3 * float(np.mean(accept_ms))
 
@@ -212,7 +227,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(kv_bytes / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": measured_traffic(),
         },
     }
 

@@ -167,6 +167,27 @@ int bass_spec_accept(int32_t B, int32_t kmax, int32_t V, const float* p, const f
                      int32_t* dev_status, void* stream);
 
 /*
+ * Draft-length heuristic (Algorithm 1 of the paper; HOST code, HOST pointers): picks the
+ * uniform draft length of the next speculative step from the numbers of drafts the sequences
+ * accepted in the last one.  If some sequence accepted all l_draft drafts the length grows by
+ * l_incre (up to l_limit) and s is cleared; otherwise it shrinks by ceil(l_draft / l_mod) + s,
+ * but not below 1 nor below the largest accepted count, and s is set to 1 (a consecutive
+ * shrink is one larger).  The paper's constants: l0 = 7, l_incre = 2, l_mod = 10, l_limit = 32.
+ *   state     in/out; initialise with bass_draft_len_init (l0 <= 0 selects the paper's 7)
+ *   n_accept  [B] host array: accepted drafts per sequence (bass_spec_accept's n_accept)
+ *   l_incre, l_mod, l_limit  <= 0 selects the paper's value
+ * Returns the new draft length (also stored in state), or a negative BASS_ERR_* code.
+ */
+typedef struct bass_draft_len_state {
+  int32_t l_draft; /* current draft length */
+  int32_t s;       /* 1 after a step that shrank the length, else 0 */
+} bass_draft_len_state;
+
+void bass_draft_len_init(bass_draft_len_state* state, int32_t l0);
+int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept, int32_t B,
+                            int32_t l_incre, int32_t l_mod, int32_t l_limit);
+
+/*
  * Tuning knob (host state, process wide): number of wavefronts the bf16/fp32 attention
  * kernel spreads the flattened (sequence, kv-head, context-block) work over.  Values are
  * clamped to [64, 8192]; 0 restores the default.  Returns the value in effect.

@@ -23,7 +23,7 @@ DTYPE_BF16, DTYPE_FP32 = 0, 1
 EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
     "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_append_verify_attention", "bass_spec_accept",
-    "bass_set_attention_waves",
+    "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
 )
 
 
@@ -36,6 +36,11 @@ class AttnDesc(ctypes.Structure):
         vals = {f: getattr(self, f) for f, _ in self._fields_}
         vals.update(kw)
         return AttnDesc(**vals)
+
+
+class DraftLenState(ctypes.Structure):
+    """Mirror of `bass_draft_len_state`."""
+    _fields_ = [("l_draft", ctypes.c_int32), ("s", ctypes.c_int32)]
 
 
 class BassError(RuntimeError):
@@ -74,6 +79,10 @@ def lib():
         L.bass_append_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_spec_accept.restype = ctypes.c_int
         L.bass_spec_accept.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_draft_len_init.restype = None
+        L.bass_draft_len_init.argtypes = [ctypes.POINTER(DraftLenState), i32]
+        L.bass_next_draft_len.restype = i32
+        L.bass_next_draft_len.argtypes = [ctypes.POINTER(DraftLenState), ctypes.POINTER(i32), i32, i32, i32, i32]
         L.bass_set_attention_waves.restype = ctypes.c_int
         L.bass_set_attention_waves.argtypes = [ctypes.c_int]
         _lib = L
@@ -90,6 +99,21 @@ def bass_status_string(code: int) -> str:
 
 def bass_set_attention_waves(waves: int) -> int:
     return int(lib().bass_set_attention_waves(int(waves)))
+
+
+def bass_draft_len_init(l0: int = 0) -> DraftLenState:
+    st = DraftLenState()
+    lib().bass_draft_len_init(ctypes.byref(st), int(l0))
+    return st
+
+
+def bass_next_draft_len(state: DraftLenState, n_accept, l_incre: int = 0, l_mod: int = 0, l_limit: int = 0) -> int:
+    """Host-side Algorithm 1 update; n_accept is a host sequence of ints."""
+    vals = [int(x) for x in n_accept]
+    arr = (ctypes.c_int32 * len(vals))(*vals)
+    r = int(lib().bass_next_draft_len(ctypes.byref(state), arr, len(vals), int(l_incre), int(l_mod), int(l_limit)))
+    _check(r if r < 0 else OK, "bass_next_draft_len")
+    return r
 
 
 def make_desc(B, kmax, Hq, Hkv, D, Lcap, dtype, scale) -> AttnDesc:

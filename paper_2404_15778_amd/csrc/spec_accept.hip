@@ -121,11 +121,20 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
   uint64_t S = 0;
   int tok = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
-    for (int t = wave; t < ntiles; t += kAcceptWaves) {
-      uint64_t w[4];
-      weights4(prow, qrow, t * kTile + 4 * lane, V, vec, w);
-      const uint64_t s = wave_sum(w[0] + w[1] + w[2] + w[3]);
-      if (lane == 0) tile_sum[t] = s;
+    // four tiles per round: all eight 16-byte loads of a round are in flight before the first sum
+    for (int t0 = wave; t0 < ntiles; t0 += 4 * kAcceptWaves) {
+      uint64_t w[4][4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = min(t0 + r * kAcceptWaves, ntiles - 1);  // a tile past the end repeats the last one, unused
+        weights4(prow, qrow, t * kTile + 4 * lane, V, vec, w[r]);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = t0 + r * kAcceptWaves;
+        const uint64_t sum = wave_sum(w[r][0] + w[r][1] + w[r][2] + w[r][3]);
+        if (t < ntiles && lane == 0) tile_sum[t] = sum;
+      }
     }
     __syncthreads();
     // every wavefront derives the total the same way (integer sums: order is irrelevant)

@@ -43,8 +43,10 @@ static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { } while (0)
 #endif
 
-static int attention_waves() {
-  int w = g_attention_waves > 0 ? g_attention_waves : kDefaultWaves;
+// many_rows: more than one 16-row query tile per kv head (grouped-query attention): partials are
+// large there, so the default spreads the work over fewer wavefronts (measured best on cfg4: 768)
+static int attention_waves(bool many_rows = false) {
+  int w = g_attention_waves > 0 ? g_attention_waves : (many_rows ? 768 : kDefaultWaves);
   if (w < 64) w = 64;
   if (w > kMaxWaves) w = kMaxWaves;
   return w & ~3;  // four wavefronts per workgroup
@@ -53,6 +55,7 @@ static int attention_waves() {
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
   int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
+  int fused_reduce;  // 1: the last-arriving wavefront merges a unit's partials; 0: a second launch does
   float scale_log2;  // scale * log2(e): scores are kept in the log2 domain
   const void* Q;
   const void* Kc;
@@ -475,6 +478,8 @@ __device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb
   for (int i = 0; i < D / 16; ++i) r.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(vb + i * 64)));
 }
 
+constexpr float kMaxSlack = 8.f;
+
 template <int D, int NT>
 struct RowState {
   f32x4 acc[NT][D / 16];
@@ -530,11 +535,18 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(st.m[nt], mx);
+    // The reference maximum of a row only moves when it would grow by more than kMaxSlack (log2
+    // units) or is still -inf.  Until then probabilities are taken relative to the old reference
+    // (so they can reach 2^kMaxSlack, harmless in fp32 / bf16), which saves rescaling the
+    // accumulators on almost every block.  (m, l, acc) stay consistent, which is all the
+    // split-context reduction needs.
+    const float m_old = st.m[nt];
+    const bool grow = mx > m_old + kMaxSlack;  // false while both are -inf
+    const float m_new = grow ? mx : m_old;
     // a row that has seen no visible token yet keeps m = -inf; subtract 0 instead so that
     // exp2(-inf - 0) = 0 and no inf - inf appears
     const float m_use = (kMasked && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_use);
+    const float alpha = grow ? __builtin_amdgcn_exp2f(m_old - m_use) : 1.f;
     float psum = 0.f;
     bf16x8 pf;
 #pragma unroll
@@ -545,12 +557,13 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     }
     st.l[nt] = st.l[nt] * alpha + psum;
     st.m[nt] = m_new;
+    if (__any(grow)) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      f32x4 a = st.acc[nt][mt];
-      a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
-      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, a, 0, 0, 0);
+      for (int mt = 0; mt < MT; ++mt) st.acc[nt][mt] *= alpha;
     }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, st.acc[nt][mt], 0, 0, 0);
   }
 }
 
@@ -818,9 +831,16 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       }
     }
     BASS_TRACE(3);
+#ifdef BASS_EXP_TRACE
+    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 11] = (hasB ? 1 : 0) + (first_new != kNoNewRows ? 2 : 0) + 4 * n;
+#endif
 
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
+    if (!p.fused_reduce) {  // a second launch merges the partials
+      x += spanA + spanB;
+      continue;
+    }
     partial_stores_done();
     BASS_TRACE(4);
     CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};
@@ -836,6 +856,56 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     BASS_TRACE(6);
     x += spanA + spanB;
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// Split-context reduction as a launch of its own, used when a kv head has many query rows
+// (grouped-query attention): a unit's partials are then tens of KiB per contributor, too much
+// for the one wavefront that happens to arrive last, so the rows are spread over the whole chip:
+// one wavefront per (unit, sweep of 8 rows).
+// ---------------------------------------------------------------------------------------
+template <int KC, int DC>
+__global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
+  const int lane = threadIdx.x & 63;
+  const int sweeps = (p.rows_max + 7) / 8;
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (long)p.B * p.Hkv * sweeps) return;
+  const int sweep = (int)(item % sweeps);
+  const int unit = (int)(item / sweeps);
+  const int b = unit / p.Hkv, kvh = unit % p.Hkv;
+  const Sched sched = make_sched(p, lane, false);
+  // first block of the unit in the flattened list: blocks of earlier sequences, then earlier heads
+  int L, nq, nb;
+  if (b < 64) {
+    L = __builtin_amdgcn_readlane(sched.L, b);
+    nq = __builtin_amdgcn_readlane(sched.nq, b);
+    nb = __builtin_amdgcn_readlane(sched.nb, b);
+  } else {
+    bool bad;
+    nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
+  }
+  if (nb == 0 || 8 * sweep >= nq * p.g) return;
+  int before = 0;  // padded blocks of sequences 0..b-1
+  if (b < 64) {
+    before = __builtin_amdgcn_readlane(sched.inc, b) - nb;
+  } else {
+    before = __builtin_amdgcn_readlane(sched.inc, 63);
+    for (int c0 = 64; c0 < b; c0 += 64) {
+      const int bb = c0 + lane;
+      int L2, nq2, nb2 = 0;
+      bool bad;
+      if (bb < b) nb2 = padded_blocks(p, seq_blocks(p, bb, L2, nq2, bad));
+      before += __builtin_amdgcn_readlane(wave_incl_scan(nb2, lane), 63);
+    }
+  }
+  CombineJob job;
+  job.u = Unit{b, kvh, L, nq, nb - p.pad, before * p.Hkv + kvh * nb};
+  const int c = blocks_per_wave(sched.total * p.Hkv, p.nwaves);
+  job.w_lo = job.u.begin / c;
+  job.w_hi = (job.u.begin + job.u.nblk - 1) / c;
+  CombineRegs<KC> regs;
+  combine_issue<KC, DC>(p, job, 8 * sweep, lane, regs);
+  combine_finish<KC, DC>(p, job, 8 * sweep, lane, regs);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1012,8 +1082,10 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
 
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
-  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves();
+  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(d->dtype == BASS_DTYPE_BF16 && rows_max > 16);
   p.pad = K_new ? g_append_pad : 0;
+  // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
+  p.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || rows_max <= 16) ? 1 : 0;
   p.scale_log2 = d->scale * 1.4426950408889634f;
   p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.Knew = K_new; p.Vnew = V_new;
   p.ctx_len = ctx_len; p.draft_len = draft_len;
@@ -1041,6 +1113,13 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
       else if (nt == 3) BASS_LAUNCH(64, 3); else BASS_LAUNCH(64, 4);
     }
 #undef BASS_LAUNCH
+  }
+  if (launch_status() != BASS_OK) return BASS_ERR_HIP;
+  if (!p.fused_reduce) {
+    const long items = (long)d->B * d->Hkv * ((rows_max + 7) / 8);
+    const dim3 rgrid((unsigned)((items + 3) / 4));
+    if (d->D == 128) hipLaunchKernelGGL((reduce_partials<2, 128>), rgrid, block, 0, s, p);
+    else hipLaunchKernelGGL((reduce_partials<1, 64>), rgrid, block, 0, s, p);
   }
   return launch_status();
 }
