@@ -234,23 +234,23 @@ __device__ inline float group16_sum(float v) {
   return v;
 }
 
-// Split-context reduction of one unit, eight query rows per sweep: two groups of four rows, 16
-// lanes per row, each lane owning KC float4 chunks of its row.  Two phases, so that the requests
-// of two sweeps can be in flight together:
+// Split-context reduction of a unit, four query rows per sweep: 16 lanes per row, each lane owning
+// KC float4 chunks of its row.  Two phases, so that the requests of two sweeps can be in flight
+// together:
 //   issue : requests, for the first 8 partials, the row's (max, sum) pairs (every lane of a row
 //           asks for all of them, so no cross-lane traffic is needed later) and the lane's
 //           output chunks -- one round trip to memory in the common case;
 //   finish: weights 2^(m_s - M) / L and the weighted sum, all lane-local; units with more than 8
 //           partials (work spread very thin) continue one partial at a time; writes O and lse.
-// The requests are straight-line code: a request for a partial or a row that does not exist is
-// given an offset beyond the buffer descriptor's size, which the hardware answers with zeros
-// without touching memory.
+// Device-scope requests cost a trip to memory each: partials that do not exist are skipped by
+// wave-uniform branches, and idle row slots get an offset beyond the buffer descriptor's size,
+// which the hardware answers with zeros without touching memory.
 template <int KC>
 struct CombineRegs {
-  bool rok[2];
-  int r[2];
-  float2 ml[2][8];
-  f32x4 a[2][8][KC];
+  bool rok;
+  int r;
+  float2 ml[8];
+  f32x4 a[8][KC];
 };
 
 struct CombineJob {
@@ -282,25 +282,24 @@ __device__ inline void combine_issue(const AttnParams& p, const CombineJob& job,
   const unsigned slot_bytes = (unsigned)p.rows_max * D * 4, ml_bytes = (unsigned)p.rows_max * 8;
   const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S8 * slot_bytes);
   const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S8 * ml_bytes);
+  c.rok = r0 + rr < rows;
+  c.r = r0 + rr;
+  const unsigned ml_off = c.rok ? (unsigned)c.r * 8 : kNoSuchOffset;
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    c.rok[q] = r0 + 4 * q + rr < rows;
-    c.r[q] = r0 + 4 * q + rr;
-    const unsigned ml_off = c.rok[q] ? (unsigned)c.r[q] * 8 : kNoSuchOffset;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) c.ml[q][j] = load_dev2(rs_ml, (unsigned)j * ml_bytes + ml_off);
+  for (int j = 0; j < 8; ++j) {
+    if (j >= S8) break;  // wave-uniform: no such partial (combine_finish never looks at it)
+    c.ml[j] = load_dev2(rs_ml, (unsigned)j * ml_bytes + ml_off);
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
       const int d = 4 * (dl + 16 * k);
-      const unsigned row_off = (c.rok[q] && d < D) ? (unsigned)(c.r[q] * D + d) * 4 : kNoSuchOffset;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) c.a[q][j][k] = load_dev4(rs, (unsigned)j * slot_bytes + row_off);
+      const unsigned row_off = (c.rok && d < D) ? (unsigned)(c.r * D + d) * 4 : kNoSuchOffset;
+      c.a[j][k] = load_dev4(rs, (unsigned)j * slot_bytes + row_off);
     }
   }
 }
 
 template <int KC, int DC>
-__device__ inline void combine_finish(const AttnParams& p, const CombineJob& job, int r0, int lane, const CombineRegs<KC>& c) {
+__device__ inline void combine_finish(const AttnParams& p, const CombineJob& job, int lane, const CombineRegs<KC>& c) {
   const Unit& u = job.u;
   const int D = DC > 0 ? DC : p.D;
   const int dl = lane & 15;
@@ -308,104 +307,89 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
   const size_t slot0 = (size_t)uniform(job.w_lo + u.b * p.Hkv + u.kvh);
   const unsigned slot_bytes = (unsigned)p.rows_max * D * 4, ml_bytes = (unsigned)p.rows_max * 8;
   const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  const int r = c.r;
+  // M = max_s m_s, L = sum_s l_s 2^(m_s - M).  A valid row has at least one partial with a
+  // visible token (token 0), so M ends finite; a partial that saw none has m = -inf, weight 0.
+  // (Idle row slots were answered with zeros.)
+  float M = -INFINITY;
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int r = c.r[q];
-    // M = max_s m_s, L = sum_s l_s 2^(m_s - M).  A valid row has at least one partial with a
-    // visible token (token 0), so M ends finite; a partial that saw none has m = -inf, weight 0.
-    float m[8];
-    float M = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      m[j] = (j < S) ? c.ml[q][j].x : -INFINITY;  // requests beyond the last partial came back as zeros
-      M = fmaxf(M, m[j]);
-    }
-    const unsigned row8 = c.rok[q] ? (unsigned)r * 8 : kNoSuchOffset;
-    if (S > 8) {
-      const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
+  for (int j = 0; j < 8; ++j)
+    if (j < S) M = fmaxf(M, c.ml[j].x);  // wave-uniform guards: partials beyond S were never requested
+  const unsigned row8 = c.rok ? (unsigned)r * 8 : kNoSuchOffset;
+  if (S > 8) {
+    const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
 #pragma unroll 1
-      for (int j = 8; j < S; ++j) M = fmaxf(M, load_dev2(rs_ml, (unsigned)j * ml_bytes + row8).x);
+    for (int j = 8; j < S; ++j) M = fmaxf(M, load_dev2(rs_ml, (unsigned)j * ml_bytes + row8).x);
+  }
+  const float Mf = (M == -INFINITY) ? 0.f : M;  // idle row slots only
+  float L = 0.f;
+  f32x4 acc[KC];
+#pragma unroll
+  for (int k = 0; k < KC; ++k) acc[k] = zero4;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (j < S) {
+      const float wgt = __builtin_amdgcn_exp2f(c.ml[j].x - Mf);
+      L = fmaf(c.ml[j].y, wgt, L);
+#pragma unroll
+      for (int k = 0; k < KC; ++k) acc[k] += c.a[j][k] * wgt;
     }
-    const float Mf = (M == -INFINITY) ? 0.f : M;  // idle row slots only
-    float wgt[8];
-    float L = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      wgt[j] = __builtin_amdgcn_exp2f(m[j] - Mf);
-      L = fmaf(c.ml[q][j].y, wgt[j], L);
-    }
-    f32x4 acc[KC];
-#pragma unroll
-    for (int k = 0; k < KC; ++k) acc[k] = zero4;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int k = 0; k < KC; ++k) acc[k] += c.a[q][j][k] * wgt[j];
-    if (S > 8) {  // further partials, one at a time
-      const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S * slot_bytes);
-      const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
+  }
+  if (S > 8) {  // further partials, one at a time
+    const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S * slot_bytes);
+    const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
 #pragma unroll 1
-      for (int j = 8; j < S; ++j) {
-        const float2 ml = load_dev2(rs_ml, (unsigned)j * ml_bytes + row8);
-        const float w = __builtin_amdgcn_exp2f(ml.x - Mf);
-        L = fmaf(ml.y, w, L);
-#pragma unroll
-        for (int k = 0; k < KC; ++k) {
-          const int d = 4 * (dl + 16 * k);
-          const unsigned row_off = (c.rok[q] && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
-          acc[k] += load_dev4(rs, (unsigned)j * slot_bytes + row_off) * w;
-        }
-      }
-    }
-    if (c.rok[q]) {
-      const float invL = 1.f / L;
-      const int i = r / p.g, hg = r % p.g;
-      const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
+    for (int j = 8; j < S; ++j) {
+      const float2 ml = load_dev2(rs_ml, (unsigned)j * ml_bytes + row8);
+      const float w = __builtin_amdgcn_exp2f(ml.x - Mf);
+      L = fmaf(ml.y, w, L);
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
         const int d = 4 * (dl + 16 * k);
-        if (d < D) *(f32x4*)(p.O + orow * D + d) = acc[k] * invL;
+        const unsigned row_off = (c.rok && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
+        acc[k] += load_dev4(rs, (unsigned)j * slot_bytes + row_off) * w;
       }
-      if (p.lse && dl == 0) p.lse[orow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
     }
+  }
+  if (c.rok) {
+    const float invL = 1.f / L;
+    const int i = r / p.g, hg = r % p.g;
+    const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      const int d = 4 * (dl + 16 * k);
+      if (d < D) *(f32x4*)(p.O + orow * D + d) = acc[k] * invL;
+    }
+    if (p.lse && dl == 0) p.lse[orow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
   }
 }
 
-// Reduction of the one or two units this wavefront completed.  The sweeps (8 rows each) of both
-// jobs are laid end to end and handled two at a time, so that two sweeps -- typically the only
-// sweep of each unit -- share one round trip to memory.
+// Reduction of the one or two units this wavefront completed.  The sweeps (4 rows each) of both
+// jobs are laid end to end and handled two at a time, so that two sweeps share one round trip.
 template <int KC, int DC>
 __device__ inline void combine_jobs(const AttnParams& p, const CombineJob& ja, bool do_a, const CombineJob& jb, bool do_b,
-                                    int lane, int wdbg = 0) {
+                                    int lane) {
   constexpr bool kOverlap = DC > 0;  // the run-time-D (fp32) variant has too many chunk registers for two sweeps
   const CombineJob& j0 = do_a ? ja : jb;  // first (or only) job
   const bool two = do_a && do_b;
-  const int n0 = (j0.u.nq * p.g + 7) / 8;
-  const int n1 = two ? (jb.u.nq * p.g + 7) / 8 : 0;
+  const int n0 = (j0.u.nq * p.g + 3) / 4;
+  const int n1 = two ? (jb.u.nq * p.g + 3) / 4 : 0;
 #pragma unroll 1
   for (int t = 0; t < n0 + n1; t += (kOverlap ? 2 : 1)) {
     const bool has_y = kOverlap && t + 1 < n0 + n1;
     const CombineJob jx = (t < n0) ? j0 : jb;
-    const int rx = (t < n0) ? 8 * t : 8 * (t - n0);
+    const int rx = (t < n0) ? 4 * t : 4 * (t - n0);
     const CombineJob jy = (t + 1 < n0) ? j0 : jb;
-    const int ry = (t + 1 < n0) ? 8 * (t + 1) : 8 * (t + 1 - n0);
+    const int ry = (t + 1 < n0) ? 4 * (t + 1) : 4 * (t + 1 - n0);
     CombineRegs<KC> cx;
     combine_issue<KC, DC>(p, jx, rx, lane, cx);
     if constexpr (kOverlap) {
       CombineRegs<KC> cy;
       if (has_y) combine_issue<KC, DC>(p, jy, ry, lane, cy);
-#ifdef BASS_EXP_TRACE
-      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 8] = wall_clock64();
-      { float probe = cx.a[0][0][0][0] + cx.ml[0][0].x; asm volatile("" :: "v"(probe)); }
-      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 9] = wall_clock64();
-#endif
-      combine_finish<KC, DC>(p, jx, rx, lane, cx);
-#ifdef BASS_EXP_TRACE
-      if (p.trace && lane == 0 && t == 0) p.trace[(size_t)wdbg * 16 + 10] = wall_clock64();
-#endif
-      if (has_y) combine_finish<KC, DC>(p, jy, ry, lane, cy);
+      combine_finish<KC, DC>(p, jx, lane, cx);
+      if (has_y) combine_finish<KC, DC>(p, jy, lane, cy);
     } else {
-      combine_finish<KC, DC>(p, jx, rx, lane, cx);
+      combine_finish<KC, DC>(p, jx, lane, cx);
     }
   }
 }
@@ -478,8 +462,6 @@ __device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb
   for (int i = 0; i < D / 16; ++i) r.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(vb + i * 64)));
 }
 
-constexpr float kMaxSlack = 8.f;
-
 template <int D, int NT>
 struct RowState {
   f32x4 acc[NT][D / 16];
@@ -535,18 +517,11 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    // The reference maximum of a row only moves when it would grow by more than kMaxSlack (log2
-    // units) or is still -inf.  Until then probabilities are taken relative to the old reference
-    // (so they can reach 2^kMaxSlack, harmless in fp32 / bf16), which saves rescaling the
-    // accumulators on almost every block.  (m, l, acc) stay consistent, which is all the
-    // split-context reduction needs.
-    const float m_old = st.m[nt];
-    const bool grow = mx > m_old + kMaxSlack;  // false while both are -inf
-    const float m_new = grow ? mx : m_old;
+    const float m_new = fmaxf(st.m[nt], mx);
     // a row that has seen no visible token yet keeps m = -inf; subtract 0 instead so that
     // exp2(-inf - 0) = 0 and no inf - inf appears
     const float m_use = (kMasked && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = grow ? __builtin_amdgcn_exp2f(m_old - m_use) : 1.f;
+    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_use);
     float psum = 0.f;
     bf16x8 pf;
 #pragma unroll
@@ -557,13 +532,9 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     }
     st.l[nt] = st.l[nt] * alpha + psum;
     st.m[nt] = m_new;
-    if (__any(grow)) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) st.acc[nt][mt] *= alpha;
-    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, st.acc[nt][mt], 0, 0, 0);
+      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, st.acc[nt][mt] * alpha, 0, 0, 0);
   }
 }
 
@@ -710,6 +681,8 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   // With one query tile there are registers to spare for a second unit's state, so a wavefront
   // whose share of blocks crosses a unit boundary keeps streaming: it parks the first unit's
   // accumulators, carries on with the second unit, and delivers both partials at the end.
+  // (Storing the first partial at the boundary instead costs about 1 us per launch: the stores
+  // sit in the ring's wait counts.)
   constexpr bool kPair = (NT == 1);
   const int lane = threadIdx.x & 63;
   const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -833,6 +806,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     BASS_TRACE(3);
 #ifdef BASS_EXP_TRACE
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 11] = (hasB ? 1 : 0) + (first_new != kNoNewRows ? 2 : 0) + 4 * n;
+    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 12] = __builtin_amdgcn_s_getreg(6164);  // XCC_ID
 #endif
 
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
@@ -851,7 +825,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
 #endif
 #ifndef BASS_EXP_NOCOMBINE
-    if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane, w);
+    if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane);
 #endif
     BASS_TRACE(6);
     x += spanA + spanB;
@@ -862,12 +836,12 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 // Split-context reduction as a launch of its own, used when a kv head has many query rows
 // (grouped-query attention): a unit's partials are then tens of KiB per contributor, too much
 // for the one wavefront that happens to arrive last, so the rows are spread over the whole chip:
-// one wavefront per (unit, sweep of 8 rows).
+// one wavefront per (unit, sweep of 4 rows).
 // ---------------------------------------------------------------------------------------
 template <int KC, int DC>
 __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   const int lane = threadIdx.x & 63;
-  const int sweeps = (p.rows_max + 7) / 8;
+  const int sweeps = (p.rows_max + 3) / 4;
   const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (item >= (long)p.B * p.Hkv * sweeps) return;
   const int sweep = (int)(item % sweeps);
@@ -884,7 +858,7 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
     bool bad;
     nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
   }
-  if (nb == 0 || 8 * sweep >= nq * p.g) return;
+  if (nb == 0 || 4 * sweep >= nq * p.g) return;
   int before = 0;  // padded blocks of sequences 0..b-1
   if (b < 64) {
     before = __builtin_amdgcn_readlane(sched.inc, b) - nb;
@@ -904,8 +878,8 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   job.w_lo = job.u.begin / c;
   job.w_hi = (job.u.begin + job.u.nblk - 1) / c;
   CombineRegs<KC> regs;
-  combine_issue<KC, DC>(p, job, 8 * sweep, lane, regs);
-  combine_finish<KC, DC>(p, job, 8 * sweep, lane, regs);
+  combine_issue<KC, DC>(p, job, 4 * sweep, lane, regs);
+  combine_finish<KC, DC>(p, job, lane, regs);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1116,7 +1090,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   }
   if (launch_status() != BASS_OK) return BASS_ERR_HIP;
   if (!p.fused_reduce) {
-    const long items = (long)d->B * d->Hkv * ((rows_max + 7) / 8);
+    const long items = (long)d->B * d->Hkv * ((rows_max + 3) / 4);
     const dim3 rgrid((unsigned)((items + 3) / 4));
     if (d->D == 128) hipLaunchKernelGGL((reduce_partials<2, 128>), rgrid, block, 0, s, p);
     else hipLaunchKernelGGL((reduce_partials<1, 64>), rgrid, block, 0, s, p);
