@@ -26,6 +26,9 @@
 // for two 16-token tiles, exactly the operand layout of the second once the V block is
 // stored in that token order, so P goes from accumulator to operand with a bf16 pack only.
 // Query rows of one kv head are (draft i, head-in-group) pairs, up to 64 rows = 4 tiles.
+#include <cstdio>
+#include <cstdlib>
+
 #include "bass_common.h"
 
 namespace bass {
@@ -36,6 +39,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 static int g_attention_waves = 0;  // 0 = default
 static int g_append_pad = 2;      // virtual blocks per unit when the append is fused (measured best: 2)
+static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
 #ifdef BASS_EXP_TRACE
 static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
@@ -462,6 +466,67 @@ __device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb
   for (int i = 0; i < D / 16; ++i) r.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(vb + i * 64)));
 }
 
+// Fused append: the step's own K/V rows of one unit (rows i < nq of K_new, V_new for sequence b,
+// kv head kvh).  The wavefront whose share holds the unit's last blocks copies those rows into its
+// own slice of LDS before it starts streaming; when it reaches the (masked) blocks the new tokens
+// belong to, it patches the fetched K and V fragments from LDS and writes the patched 16-byte
+// chunks back into the cache (plain stores that nobody waits for: no other wavefront reads those
+// blocks in this launch).  The patch needs no global load, so the ring of outstanding K/V fetches
+// is never drained for it.
+extern __shared__ __align__(16) unsigned char new_rows_lds[];
+
+struct NewRows {
+  unsigned k_off, v_off;  // byte offsets of the unit's K and V rows ([row][D] bf16) in new_rows_lds
+  int L, nq;
+};
+
+// A pass copies 128 16-byte chunks (2 per lane and tensor): 8 rows of 128 head elements.  The first
+// pass overlaps the first K/V fetches; longer drafts take further passes, one after the other.
+// The host keeps kmax * D <= kMaxStagedElems so that a workgroup's slices fit in 64 KiB of LDS.
+constexpr int kStageLoads = 2;
+constexpr int kStagePass = kStageLoads * 64;
+constexpr int kMaxStagedElems = 2048;
+
+struct StageRegs {
+  u32x4 k[kStageLoads], v[kStageLoads];
+};
+
+// Loads of a unit's nq new rows, chunk c = c0 + 64 i + lane: row c / (D/8), head elements 8 (c % (D/8)) ..
+template <int D>
+__device__ inline void stage_issue(const AttnParams& p, const Unit& u, int c0, int lane, StageRegs& sr) {
+  constexpr int CPR = D / 8;
+  const size_t row_stride = (size_t)p.Hkv * D;
+  const size_t first = ((size_t)u.b * p.kmax * p.Hkv + u.kvh) * D;
+  const uint16_t* kn = (const uint16_t*)p.Knew + first;
+  const uint16_t* vn = (const uint16_t*)p.Vnew + first;
+  const int nchunks = u.nq * CPR;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int i = 0; i < kStageLoads; ++i) {
+    sr.k[i] = zero;
+    sr.v[i] = zero;
+    if (c0 + i * 64 < nchunks) {  // wave-uniform
+      const int c = min(c0 + i * 64 + lane, nchunks - 1);  // lanes past the end repeat the last chunk
+      const size_t e = (size_t)(c / CPR) * row_stride + 8 * (c % CPR);
+      sr.k[i] = *(const u32x4*)(kn + e);
+      sr.v[i] = *(const u32x4*)(vn + e);
+    }
+  }
+}
+
+template <int D>
+__device__ inline void stage_commit(const Unit& u, int c0, int lane, const StageRegs& sr, const NewRows& nr) {
+  const int nchunks = u.nq * (D / 8);
+#pragma unroll
+  for (int i = 0; i < kStageLoads; ++i) {
+    const int c = c0 + i * 64 + lane;
+    if (c < nchunks) {
+      *(u32x4*)&new_rows_lds[nr.k_off + 16 * c] = sr.k[i];
+      *(u32x4*)&new_rows_lds[nr.v_off + 16 * c] = sr.v[i];
+    }
+  }
+}
+
 template <int D, int NT>
 struct RowState {
   f32x4 acc[NT][D / 16];
@@ -473,9 +538,43 @@ struct RowState {
 // causal limits and the valid-token bound apply (wave-uniform choice).
 template <int D, int NT, bool kMasked>
 __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int tok0,
-                                  int n_valid, const int (&lim)[NT], float scale_log2, int lane) {
+                                  int n_valid, const int (&lim)[NT], float scale_log2, int lane,
+                                  bool fused = false, const NewRows& nr = NewRows{}, uint4* kdst = nullptr,
+                                  uint4* vdst = nullptr) {
   constexpr int KS = D / 32, MT = D / 16;
   const int grp = lane >> 4;
+  bool v_new = false;  // this lane's V chunks hold a new token
+  if (kMasked && fused) {
+    const int dr = lane & 15;
+    // K: fragment tl * KS + t of a lane is token 16 tl + lane % 16, head elements 32 t + 8 grp .. + 7:
+    // one 16-byte chunk of the new row
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl) {
+      const int i = tok0 + 16 * tl + dr - nr.L;
+      if (i >= 0 && i < nr.nq) {
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+          const u32x4 kv = *(const u32x4*)&new_rows_lds[nr.k_off + 2 * (i * D + 32 * t + 8 * grp)];
+          r.k[tl * KS + t] = __builtin_bit_cast(uint4, kv);
+          *(u32x4*)(kdst + (tl * KS + t) * 64) = kv;
+        }
+      }
+    }
+    // V: slot j of a lane is token 4 grp + j (j < 4) or 16 + 4 grp + j - 4, head element 16 mt + lane % 16
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = tok0 + (j < 4 ? 4 * grp + j : 16 + 4 * grp + (j - 4)) - nr.L;
+      if (i >= 0 && i < nr.nq) {
+        v_new = true;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint32_t v = *(const uint16_t*)&new_rows_lds[nr.v_off + 2 * (i * D + 16 * mt + dr)];
+          uint32_t* wv = (uint32_t*)&r.v[mt];
+          wv[j >> 1] = (j & 1) ? (wv[j >> 1] & 0x0000FFFFu) | (v << 16) : (wv[j >> 1] & 0xFFFF0000u) | v;
+        }
+      }
+    }
+  }
   if (kMasked) {
     // stale cache rows (token >= n_valid) may hold anything, NaN included: zero them in V so
     // that 0 * garbage cannot reach the accumulator.  Word w of a lane holds slots 2w, 2w+1.
@@ -491,6 +590,10 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
         if (t_lo + 1 < n_valid) keep |= 0xFFFF0000u;
         wv[wd] &= keep;
       }
+    }
+    if (v_new) {  // the patched chunks go back into the cache (stale slots zeroed: they may hold anything)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) *(u32x4*)(vdst + mt * 64) = __builtin_bit_cast(u32x4, r.v[mt]);
     }
   }
 #pragma unroll
@@ -540,66 +643,19 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
 
 template <int D, int NT>
 __device__ inline void block_dispatch(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int blk,
-                                      int L, int n_valid, const int (&lim)[NT], float scale_log2, int lane) {
+                                      int L, int n_valid, const int (&lim)[NT], float scale_log2, int lane,
+                                      bool fused, const NewRows& nr, uint4* kdst, uint4* vdst) {
   const int tok0 = blk * kBlockTokens;
-  if (tok0 + kBlockTokens - 1 <= L)  // every token of the block is visible to every query
+  // plain step: every token of the block is visible to every query (tokens <= L) and, with a fused
+  // append, none of them is new (tokens < L)
+  if (tok0 + kBlockTokens - 1 < L + (fused ? 0 : 1))
     block_step<D, NT, false>(r, qf, st, tok0, n_valid, lim, scale_log2, lane);
   else
-    block_step<D, NT, true>(r, qf, st, tok0, n_valid, lim, scale_log2, lane);
+    block_step<D, NT, true>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, fused, nr, kdst, vdst);
 }
 
-// Fused append (optional).  The rows of this step's own tokens are copied into the cache by the
-// wavefront whose share of blocks holds them, before it starts streaming: every cache line is
-// then written and read by the same wavefront (store, wait for the acknowledgement, load), and
-// no other wavefront reads those blocks in this launch.  Returns whether anything was written.
-template <int D>
-__device__ inline bool append_own_rows_bf16(const AttnParams& p, const Unit& u, int blk_lo, int nblk, int lane) {
-  const int t_lo = max(u.L, blk_lo * kBlockTokens);
-  const int t_hi = min(u.L + u.nq, (blk_lo + nblk) * kBlockTokens);
-  if (t_lo >= t_hi) return false;
-  uint16_t* kc = (uint16_t*)const_cast<void*>(p.Kc);
-  uint16_t* vc = (uint16_t*)const_cast<void*>(p.Vc);
-  const uint16_t* kn = (const uint16_t*)p.Knew + (((size_t)u.b * p.kmax) * p.Hkv + u.kvh) * D;
-  const uint16_t* vn = (const uint16_t*)p.Vnew + (((size_t)u.b * p.kmax) * p.Hkv + u.kvh) * D;
-  const size_t row_stride = (size_t)p.Hkv * D;  // between consecutive rows of one (sequence, kv head)
-  const size_t unit_base = ((size_t)u.b * p.Hkv + u.kvh) * p.nblk_cap * ((size_t)kBlockTokens * D);
-  auto cache_off = [&](int t) { return unit_base + (size_t)(t / kBlockTokens) * ((size_t)kBlockTokens * D); };
-  constexpr int kLanesPerRow = D / 8, kRowsPerPass = 64 / kLanesPerRow, kPasses = 8 / kRowsPerPass;
-  // Eight tokens per round; all loads of a round are issued before its first store.  Loads are
-  // unconditional (a row index past the end is clamped to the last row) and only the stores are
-  // guarded, so that the staging values stay in registers.
-  for (int t0 = t_lo; t0 < t_hi; t0 += 8) {
-    u32x4 kv[kPasses];
-    unsigned vv[8][D / 64];
-#pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) {  // K: a lane copies one 16-byte chunk of one row
-      const int t = min(t0 + ps * kRowsPerPass + lane / kLanesPerRow, t_hi - 1);
-      kv[ps] = *(const u32x4*)(kn + (size_t)(t - u.L) * row_stride + 8 * (lane % kLanesPerRow));
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {  // V: a lane copies elements lane, lane + 64 of every row
-      const int t = min(t0 + j, t_hi - 1);
-#pragma unroll
-      for (int h = 0; h < D / 64; ++h) vv[j][h] = vn[(size_t)(t - u.L) * row_stride + lane + 64 * h];
-    }
-#pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) {
-      const int t = t0 + ps * kRowsPerPass + lane / kLanesPerRow;
-      if (t < t_hi) *(u32x4*)(kc + cache_off(t) + k_elem_offset(D, t % kBlockTokens, 8 * (lane % kLanesPerRow))) = kv[ps];
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int t = t0 + j;
-      if (t < t_hi) {
-#pragma unroll
-        for (int h = 0; h < D / 64; ++h)
-          vc[cache_off(t) + v_elem_offset(D, t % kBlockTokens, lane + 64 * h)] = (uint16_t)vv[j][h];
-      }
-    }
-  }
-  return true;
-}
-
+// fp32 path: the wavefront whose share holds the new rows copies them into the (token-major) cache
+// and waits for the stores before it fetches those rows; nobody else reads them in this launch.
 __device__ inline bool append_own_rows_fp32(const AttnParams& p, const Unit& u, int blk_lo, int nblk, int lane) {
   const int t_lo = max(u.L, blk_lo * kBlockTokens);
   const int t_hi = min(u.L + u.nq, (blk_lo + nblk) * kBlockTokens);
@@ -726,6 +782,37 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     clear_state<D, NT>(st);
     int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
 
+    // fused append: the units whose new tokens lie in our blocks get their rows staged in LDS
+    const bool fused = p.Knew != nullptr;
+    const unsigned lds_rows = (unsigned)p.kmax * D * 2;  // bytes of one unit's K (or V) rows
+    const unsigned lds_base = (threadIdx.x >> 6) * 4 * lds_rows;
+    const NewRows newA{lds_base, lds_base + lds_rows, uA.L, uA.nq};
+    const NewRows newB{lds_base + 2 * lds_rows, lds_base + 3 * lds_rows, uB.L, uB.nq};
+    NewRows cur_new = newA;
+    const bool stageA = fused && uA.nq > 0 && (x - uA.begin + nA) * kBlockTokens > uA.L;
+    const bool stageB = fused && hasB && uB.nq > 0 && nB * kBlockTokens > uB.L;
+    // one set of staging registers: a share that holds the new tokens of both its units is rare (the
+    // second unit then lies wholly inside the share) and stages the second unit's rows afterwards
+    const bool stage1 = stageA || stageB;
+    const Unit& u1 = stageA ? uA : uB;
+    const NewRows& new1 = stageA ? newA : newB;
+    StageRegs sr;
+    if (stage1) stage_issue<D>(p, u1, 0, lane, sr);
+    // what is left after the overlapped pass (drafts of more than 8 rows, a second unit): rare
+    auto stage_rest = [&]() {
+      for (int c0 = kStagePass; c0 < u1.nq * (D / 8); c0 += kStagePass) {
+        StageRegs sr2;
+        stage_issue<D>(p, u1, c0, lane, sr2);
+        stage_commit<D>(u1, c0, lane, sr2, new1);
+      }
+      if (stageA && stageB)
+        for (int c0 = 0; c0 < uB.nq * (D / 8); c0 += kStagePass) {
+          StageRegs sr2;
+          stage_issue<D>(p, uB, c0, lane, sr2);
+          stage_commit<D>(uB, c0, lane, sr2, newB);
+        }
+    };
+
     // element offsets (in uint4) of step s inside the K and V caches
     const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + (x - uA.begin)) * kBlkVec;
     const ptrdiff_t vecB = (((ptrdiff_t)uB.b * p.Hkv + uB.kvh) * p.nblk_cap - nA) * kBlkVec;
@@ -750,39 +837,30 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
           cur_L = uB.L;
           cur_valid = uB.L + uB.nq;
           cur_blk = -nA;
+          cur_new = newB;
         }
       }
+      const ptrdiff_t own = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec + lane;  // this lane's chunks of block s
+      uint4* kdst = (uint4*)const_cast<void*>(p.Kc) + own;
+      uint4* vdst = (uint4*)const_cast<void*>(p.Vc) + own;
 #ifdef BASS_EXP_NOCOMPUTE
       unsigned xx = 0;
       for (int i = 0; i < 2 * (D / 32); ++i) xx ^= r.k[i].x ^ r.k[i].y ^ r.k[i].z ^ r.k[i].w;
       for (int i = 0; i < D / 16; ++i) xx ^= r.v[i].x ^ r.v[i].y ^ r.v[i].z ^ r.v[i].w;
       st.l[0] += __uint_as_float(xx & 0x3f800000u);
 #else
-      block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane);
+      block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
 #endif
     };
-    // Fused append: this share's own new rows go into the cache before the blocks that hold them
-    // are fetched.  They sit at the end of a unit, so normally the first fetches can be issued
-    // first and the store acknowledgements are awaited while those fetches are in flight.
-    constexpr int kPrefetched = (NT <= 2) ? 2 : 1;  // blocks fetched before the loop starts
-    constexpr int kNoNewRows = 1 << 30;
-    int first_new = kNoNewRows;                      // first step whose block holds a new row
-    if (p.Knew) {
-      if (uA.L / kBlockTokens < (x - uA.begin) + nA) first_new = max(uA.L / kBlockTokens - (x - uA.begin), 0);
-      else if (hasB && uB.L / kBlockTokens < nB) first_new = nA + uB.L / kBlockTokens;
-    }
-    auto append_rows = [&]() {
-      bool wrote = append_own_rows_bf16<D>(p, uA, x - uA.begin, nA, lane);
-      if (hasB) wrote |= append_own_rows_bf16<D>(p, uB, 0, nB, lane);
-      if (wrote) partial_stores_done();  // acknowledged before the same lines are fetched
-    };
-    if (first_new < kPrefetched) append_rows();  // (never without K_new: first_new stays kNoNewRows)
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
       KvRegs<D> r0, r1, r2;
       fetch(r0, 0);
       fetch(r1, 1);
-      if (first_new >= kPrefetched && first_new != kNoNewRows) append_rows();
+      if (stage1) {
+        stage_commit<D>(u1, 0, lane, sr, new1);  // these loads were issued before the fetches
+        stage_rest();
+      }
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
@@ -795,7 +873,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       // many query rows need the registers for accumulators: two-deep ring
       KvRegs<D> r0, r1;
       fetch(r0, 0);
-      if (first_new >= kPrefetched && first_new != kNoNewRows) append_rows();
+      if (stage1) {
+        stage_commit<D>(u1, 0, lane, sr, new1);
+        stage_rest();
+      }
       for (int s = 0; s < n; s += 2) {
         fetch(r1, s + 1);
         step(r0, s);
@@ -805,7 +886,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     }
     BASS_TRACE(3);
 #ifdef BASS_EXP_TRACE
-    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 11] = (hasB ? 1 : 0) + (first_new != kNoNewRows ? 2 : 0) + 4 * n;
+    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 11] = (hasB ? 1 : 0) + (fused && ((x - uA.begin + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n;
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 12] = __builtin_amdgcn_s_getreg(6164);  // XCC_ID
 #endif
 
@@ -1023,7 +1104,7 @@ extern "C" void bass_debug_set_trace(void* ptr) { bass::g_trace = (long long*)pt
 #endif
 
 #ifdef BASS_EXP_TRACE
-extern "C" void bass_debug_set_pad(int pad) { bass::g_append_pad = pad; }
+extern "C" void bass_debug_set_pad(int pad) { bass::g_append_pad = pad; bass::g_plain_pad = pad; }
 #endif
 
 extern "C" int bass_set_attention_waves(int waves) {
@@ -1037,6 +1118,20 @@ extern "C" size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* d)
 }
 
 namespace bass {
+
+// BASS_ATTN_PAD="<fused>,<plain>" overrides the virtual blocks per unit (tuning experiments).
+static void read_pad_override() {
+  static bool done = false;
+  if (done) return;
+  done = true;
+  if (const char* e = getenv("BASS_ATTN_PAD")) {
+    int a = -1, b = -1;
+    if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8) {
+      g_append_pad = a;
+      g_plain_pad = b;
+    }
+  }
+}
 
 static int launch_attention(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
                             const void* Kcache, const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
@@ -1054,10 +1149,11 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   if ((int64_t)rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
   if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
 
+  read_pad_override();
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(d->dtype == BASS_DTYPE_BF16 && rows_max > 16);
-  p.pad = K_new ? g_append_pad : 0;
+  p.pad = K_new ? g_append_pad : g_plain_pad;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
   p.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || rows_max <= 16) ? 1 : 0;
   p.scale_log2 = d->scale * 1.4426950408889634f;
@@ -1078,7 +1174,9 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
   } else {
     const int nt = (rows_max + 15) / 16;
-#define BASS_LAUNCH(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN>), grid, block, 0, s, p)
+    // LDS slice per wavefront of a fused append: K and V rows of two units
+    const size_t lds = K_new ? (size_t)4 * 4 * d->kmax * d->D * 2 : 0;
+#define BASS_LAUNCH(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN>), grid, block, lds, s, p)
     if (d->D == 128) {
       if (nt == 1) BASS_LAUNCH(128, 1); else if (nt == 2) BASS_LAUNCH(128, 2);
       else if (nt == 3) BASS_LAUNCH(128, 3); else BASS_LAUNCH(128, 4);
@@ -1112,6 +1210,13 @@ extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void*
                                             const int32_t* draft_len, float* O, float* lse, void* workspace,
                                             size_t workspace_bytes, int32_t* dev_status, void* stream) {
   if (!K_new || !V_new) return BASS_ERR_INVALID_ARG;
+  if (d && d->dtype == BASS_DTYPE_BF16 && (int64_t)d->kmax * d->D > bass::kMaxStagedElems) {
+    // more new rows than a wavefront stages in LDS: append with a launch of its own
+    const int rc = bass_kv_append(d, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, dev_status, stream);
+    if (rc != BASS_OK) return rc;
+    return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                  workspace_bytes, dev_status, stream);
+  }
   return bass::launch_attention(d, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
                                 workspace_bytes, dev_status, stream);
 }

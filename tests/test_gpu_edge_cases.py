@@ -74,6 +74,32 @@ def test_largest_row_count_bf16(hip):
     check(hip, w, fused=True)
 
 
+@pytest.mark.parametrize("D,kmax,Hq,Hkv", [(128, 12, 4, 4), (128, 16, 2, 2), (64, 32, 2, 2), (128, 20, 2, 2),
+                                            (64, 24, 4, 2), (128, 9, 2, 1)])
+@pytest.mark.parametrize("waves", [0, 64])
+def test_fused_append_with_long_drafts(hip, D, kmax, Hq, Hkv, waves):
+    # more than 8 new rows of 128 elements take several copies inside the launch; beyond
+    # kmax * D = 2048 the append runs as a launch of its own: results and caches are the same
+    import torch
+    import paper_2404_15778_amd as bass
+    ctx = [100, 37, 31, 0, 60]
+    nq = [kmax, kmax - 3, 9, kmax, 1]
+    w = wl.make_attention("long", 5, Hq, Hkv, D, "bf16", ctx, nq, 21, kmax=kmax, Lcap=160)
+    bass.bass_set_attention_waves(waves)
+    try:
+        _, da = check(hip, w, fused=True)
+    finally:
+        bass.bass_set_attention_waves(0)
+    total = w.ctx_len + w.draft_len
+    K, V = da.gather(hip.i32(np.zeros(w.B)), hip.i32(total), int(total.max()))
+    torch.cuda.synchronize()
+    K, V = hip.to_host(K), hip.to_host(V)
+    for b in range(w.B):
+        t = int(total[b])
+        np.testing.assert_array_equal(K[b, :t], w.K[b, :t])
+        np.testing.assert_array_equal(V[b, :t], w.V[b, :t])
+
+
 def test_lengths_outside_the_cache_are_clamped_and_reported(hip):
     import torch
     import paper_2404_15778_amd as bass
