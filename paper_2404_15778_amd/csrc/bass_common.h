@@ -10,7 +10,10 @@ namespace bass {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kBlockTokens = 32;   // tokens per cache block (one PV contraction step of the bf16 MFMA)
 constexpr int kMaxWaves = 8192;    // upper bound of the attention work spread (sizes the workspace)
-constexpr int kDefaultWaves = 1024;  // 256 CUs x 4 SIMDs: one fat wavefront per SIMD
+// The registers of the streaming kernel allow one wavefront per SIMD (256 CUs x 4 SIMDs = 1024
+// resident wavefronts).  Measured on the paper-shaped batches, three quarters of that is fastest:
+// the memory system is saturated either way, and fewer wavefronts mean fewer partials to merge.
+constexpr int kDefaultWaves = 768;
 
 // ---------------------------------------------------------------------------------------
 // bf16 cache layout (library-owned).  A cache is [B][Hkv][nblk] blocks of 32 tokens; a block

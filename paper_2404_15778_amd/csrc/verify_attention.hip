@@ -38,8 +38,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 static int g_attention_waves = 0;  // 0 = default
-static int g_append_pad = 2;      // virtual blocks per unit when the append is fused (measured best: 2)
+static int g_append_pad = 3;      // virtual blocks per unit when the append is fused (measured best: 3)
 static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
+static int g_wpw = 4;             // wavefronts per workgroup
 #ifdef BASS_EXP_TRACE
 static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
@@ -47,17 +48,18 @@ static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { } while (0)
 #endif
 
-// many_rows: more than one 16-row query tile per kv head (grouped-query attention): partials are
-// large there, so the default spreads the work over fewer wavefronts (measured best on cfg4: 768)
+// many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
+// launch merges the partials there, and a slightly wider spread measured best (896)
 static int attention_waves(bool many_rows = false) {
-  int w = g_attention_waves > 0 ? g_attention_waves : (many_rows ? 768 : kDefaultWaves);
+  int w = g_attention_waves > 0 ? g_attention_waves : (many_rows ? 896 : kDefaultWaves);
   if (w < 64) w = 64;
   if (w > kMaxWaves) w = kMaxWaves;
-  return w & ~3;  // four wavefronts per workgroup
+  return w - w % g_wpw;
 }
 
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
+  int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
   int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
   int fused_reduce;  // 1: the last-arriving wavefront merges a unit's partials; 0: a second launch does
   float scale_log2;  // scale * log2(e): scores are kept in the log2 domain
@@ -164,7 +166,17 @@ __device__ inline Unit locate(const AttnParams& p, const Sched& s, int x, int la
   }
 }
 
-__device__ inline int blocks_per_wave(int total, int nwaves) { return total > 0 ? (total + nwaves - 1) / nwaves : 1; }
+// Even division of the flattened block list: wavefronts 0 .. rem-1 take per + 1 consecutive blocks,
+// the others per (every wavefront works, and no share is more than one block longer than another).
+struct Split {
+  int per, rem;
+  __device__ int first(int w) const { return w * per + min(w, rem); }  // first block of wavefront w
+  __device__ int owner(int x) const {                                   // wavefront that holds block x
+    const int big = rem * (per + 1);
+    return x < big ? x / (per + 1) : rem + (x - big) / max(per, 1);
+  }
+};
+__device__ inline Split make_split(int total, int nwaves) { return Split{total / nwaves, total % nwaves}; }
 
 // Partials travel between wavefronts that may sit on different XCDs, whose L2 caches are not
 // coherent with each other for ordinary accesses.  Instead of device-scope fences (which write
@@ -405,19 +417,19 @@ __device__ inline void partial_stores_done() { __builtin_amdgcn_fence(__ATOMIC_R
 // Counts this wavefront's arrival at one or two units (after partial_stores_done).  A job's
 // `last` result is true if this wavefront delivered the unit's last partial: it then owns the
 // reduction over wavefronts w_lo..w_hi.  Both counters are bumped before either result is awaited.
-__device__ inline int32_t* arrival_counter(const AttnParams& p, int c, CombineJob& j, int& nparts) {
-  j.w_lo = j.u.begin / c;
-  j.w_hi = (j.u.begin + j.u.nblk - 1) / c;
+__device__ inline int32_t* arrival_counter(const AttnParams& p, const Split& sp, CombineJob& j, int& nparts) {
+  j.w_lo = sp.owner(j.u.begin);
+  j.w_hi = sp.owner(j.u.begin + j.u.nblk - 1);
   nparts = j.w_hi - j.w_lo + 1;
   return p.counters + (size_t)j.u.b * p.Hkv + j.u.kvh;
 }
 
-__device__ inline void arrive(const AttnParams& p, int c, int lane, CombineJob& ja, bool& last_a, bool has_b, CombineJob& jb,
+__device__ inline void arrive(const AttnParams& p, const Split& sp, int lane, CombineJob& ja, bool& last_a, bool has_b, CombineJob& jb,
                               bool& last_b) {
   int na, nb = 1, old_a = 0, old_b = 0;
-  int32_t* ctr_a = arrival_counter(p, c, ja, na);
+  int32_t* ctr_a = arrival_counter(p, sp, ja, na);
   int32_t* ctr_b = ctr_a;
-  if (has_b) ctr_b = arrival_counter(p, c, jb, nb);
+  if (has_b) ctr_b = arrival_counter(p, sp, jb, nb);
   if (na > 1 && lane == 0) old_a = __hip_atomic_fetch_add(ctr_a, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (has_b && nb > 1 && lane == 0) old_b = __hip_atomic_fetch_add(ctr_b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   last_a = na == 1 || __builtin_amdgcn_readfirstlane(old_a) == na - 1;
@@ -741,15 +753,15 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   // sit in the ring's wait counts.)
   constexpr bool kPair = (NT == 1);
   const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int w = blockIdx.x * p.wpw + (threadIdx.x >> 6);
   const int col = lane & 15, grp = lane >> 4;
   BASS_TRACE(0);
 
   const Sched sched = make_sched(p, lane, w == 0);
   const int total = sched.total * p.Hkv;
-  const int c = blocks_per_wave(total, p.nwaves);
-  int x = w * c;
-  const int x_end = min(total, x + c);
+  const Split sp = make_split(total, p.nwaves);
+  int x = sp.first(w);
+  const int x_end = sp.first(w + 1);
   zero_unused_rows(p, sched, w, lane);
   BASS_TRACE(1);
 
@@ -900,7 +912,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     BASS_TRACE(4);
     CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};
     bool lastA, lastB;
-    arrive(p, c, lane, ja, lastA, hasB, jb, lastB);
+    arrive(p, sp, lane, ja, lastA, hasB, jb, lastB);
     BASS_TRACE(5);
 #ifdef BASS_EXP_TRACE
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
@@ -955,9 +967,9 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   }
   CombineJob job;
   job.u = Unit{b, kvh, L, nq, nb - p.pad, before * p.Hkv + kvh * nb};
-  const int c = blocks_per_wave(sched.total * p.Hkv, p.nwaves);
-  job.w_lo = job.u.begin / c;
-  job.w_hi = (job.u.begin + job.u.nblk - 1) / c;
+  const Split sp = make_split(sched.total * p.Hkv, p.nwaves);
+  job.w_lo = sp.owner(job.u.begin);
+  job.w_hi = sp.owner(job.u.begin + job.u.nblk - 1);
   CombineRegs<KC> regs;
   combine_issue<KC, DC>(p, job, 4 * sweep, lane, regs);
   combine_finish<KC, DC>(p, job, lane, regs);
@@ -972,15 +984,15 @@ constexpr int kRowChunk = 8;
 
 __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
   const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int w = blockIdx.x * p.wpw + (threadIdx.x >> 6);
   const int D = p.D;
   const int nd = (D + 63) / 64;  // head elements per lane (<= 4)
 
   const Sched sched = make_sched(p, lane, w == 0);
   const int total = sched.total * p.Hkv;
-  const int c = blocks_per_wave(total, p.nwaves);
-  int x = w * c;
-  const int x_end = min(total, x + c);
+  const Split sp = make_split(total, p.nwaves);
+  int x = sp.first(w);
+  const int x_end = sp.first(w + 1);
   zero_unused_rows(p, sched, w, lane);
 
   while (x < x_end) {
@@ -1080,7 +1092,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
     partial_stores_done();
     CombineJob job{u, 0, 0};
     bool last, unused;
-    arrive(p, c, lane, job, last, false, job, unused);
+    arrive(p, sp, lane, job, last, false, job, unused);
     if (last) combine_jobs<4, 0>(p, job, true, job, false, lane);
     x += span;
   }
@@ -1125,10 +1137,11 @@ static void read_pad_override() {
   if (done) return;
   done = true;
   if (const char* e = getenv("BASS_ATTN_PAD")) {
-    int a = -1, b = -1;
-    if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8) {
+    int a = -1, b = -1, c = 4;
+    if (sscanf(e, "%d,%d,%d", &a, &b, &c) >= 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8 && c >= 1 && c <= 4) {
       g_append_pad = a;
       g_plain_pad = b;
+      g_wpw = c;
     }
   }
 }
@@ -1169,13 +1182,14 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   p.part_ml = p.part_acc + slots * rows_max * d->D;
 
   hipStream_t s = (hipStream_t)stream;
-  const dim3 grid(p.nwaves / 4), block(256);
+  p.wpw = g_wpw;
+  const dim3 grid(p.nwaves / p.wpw), block(64 * p.wpw);
   if (d->dtype == BASS_DTYPE_FP32) {
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
   } else {
     const int nt = (rows_max + 15) / 16;
     // LDS slice per wavefront of a fused append: K and V rows of two units
-    const size_t lds = K_new ? (size_t)4 * 4 * d->kmax * d->D * 2 : 0;
+    const size_t lds = K_new ? (size_t)p.wpw * 4 * d->kmax * d->D * 2 : 0;
 #define BASS_LAUNCH(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN>), grid, block, lds, s, p)
     if (d->D == 128) {
       if (nt == 1) BASS_LAUNCH(128, 1); else if (nt == 2) BASS_LAUNCH(128, 2);
@@ -1190,8 +1204,8 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   if (!p.fused_reduce) {
     const long items = (long)d->B * d->Hkv * ((rows_max + 3) / 4);
     const dim3 rgrid((unsigned)((items + 3) / 4));
-    if (d->D == 128) hipLaunchKernelGGL((reduce_partials<2, 128>), rgrid, block, 0, s, p);
-    else hipLaunchKernelGGL((reduce_partials<1, 64>), rgrid, block, 0, s, p);
+    if (d->D == 128) hipLaunchKernelGGL((reduce_partials<2, 128>), rgrid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((reduce_partials<1, 64>), rgrid, dim3(256), 0, s, p);
   }
   return launch_status();
 }

@@ -86,4 +86,4 @@ def test_attention_waves_knob_is_clamped():
     assert bass.bass_set_attention_waves(1) == 64
     assert bass.bass_set_attention_waves(10**6) == 8192
     assert bass.bass_set_attention_waves(1022) == 1020
-    assert bass.bass_set_attention_waves(0) == 1024
+    assert bass.bass_set_attention_waves(0) == 768
