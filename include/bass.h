@@ -124,8 +124,31 @@ int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void*
                           int32_t* dev_status, void* stream);
 
 /*
- * The two calls above in ONE launch: appends rows i < draft_len[b] of K_new, V_new
- * [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
+ * The paper's two ways of batching ragged attention (Section 3.2), as launch variants of the
+ * same kernel, for comparison with bass_verify_attention; arguments and results as there.
+ *
+ * bass_verify_attention_pad (BASS-PAD): one launch in which every active sequence is
+ * processed over max(padded_len, ctx_len[b] + draft_len[b]) cache positions (at most Lcap):
+ * K, V and P are treated as padded to a common length, the padded positions are read, take
+ * part in the products and get probability exactly zero.  With padded_len = the longest
+ * sequence of the batch this is the paper's scheme; padded_len = 0 is bass_verify_attention.
+ * (fp32 caches: padded positions are skipped, not read.)
+ *
+ * bass_verify_attention_split (BASS-SPLIT): one launch per sequence, each over that sequence's
+ * own length; no wasted work, B launches.  The workspace of the whole batch is passed and shared.
+ */
+int bass_verify_attention_pad(const bass_attn_desc* desc, const void* Q, const void* Kcache,
+                              const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                              int32_t padded_len, float* O, float* lse, void* workspace,
+                              size_t workspace_bytes, int32_t* dev_status, void* stream);
+int bass_verify_attention_split(const bass_attn_desc* desc, const void* Q, const void* Kcache,
+                                const void* Vcache, const int32_t* ctx_len,
+                                const int32_t* draft_len, float* O, float* lse, void* workspace,
+                                size_t workspace_bytes, int32_t* dev_status, void* stream);
+
+/*
+ * bass_kv_append and bass_verify_attention in ONE launch: appends rows i < draft_len[b] of K_new,
+ * V_new [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
  * bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, ...) would, and computes
  * bass_verify_attention over the updated caches.  The cache contents are identical to those after
  * the two separate calls; O and lse agree with them up to rounding (the fused launch cuts the

@@ -22,7 +22,8 @@ DTYPE_BF16, DTYPE_FP32 = 0, 1
 # every symbol include/bass.h declares
 EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
-    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_append_verify_attention", "bass_spec_accept",
+    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_verify_attention_pad",
+    "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
 )
 
@@ -75,6 +76,10 @@ def lib():
         L.bass_kv_gather.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_verify_attention.restype = ctypes.c_int
         L.bass_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
+        L.bass_verify_attention_pad.restype = ctypes.c_int
+        L.bass_verify_attention_pad.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp, vp]
+        L.bass_verify_attention_split.restype = ctypes.c_int
+        L.bass_verify_attention_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_append_verify_attention.restype = ctypes.c_int
         L.bass_append_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_spec_accept.restype = ctypes.c_int
@@ -214,6 +219,38 @@ def bass_verify_attention(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, w
         _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
         ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
         _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_verify_attention")
+
+
+def _verify_args(desc, Q, Kcache, Vcache, ctx_len, draft_len):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    return (ctypes.byref(desc), _dev(Q, "Q", _elt_dtype(desc), qshape),
+            _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+            _dev(ctx_len, "ctx_len", torch.int32, (desc.B,)), _dev(draft_len, "draft_len", torch.int32, (desc.B,)))
+
+
+def _result_args(desc, O, lse, workspace, dev_status, stream):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    if workspace is None or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous GPU tensor")
+    return (_dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
+            ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+            _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream))
+
+
+def bass_verify_attention_pad(desc, Q, Kcache, Vcache, ctx_len, draft_len, padded_len, O, lse, workspace,
+                              dev_status=None, stream=None):
+    _check(lib().bass_verify_attention_pad(
+        *_verify_args(desc, Q, Kcache, Vcache, ctx_len, draft_len), ctypes.c_int32(int(padded_len)),
+        *_result_args(desc, O, lse, workspace, dev_status, stream)), "bass_verify_attention_pad")
+
+
+def bass_verify_attention_split(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace, dev_status=None,
+                                stream=None):
+    _check(lib().bass_verify_attention_split(
+        *_verify_args(desc, Q, Kcache, Vcache, ctx_len, draft_len),
+        *_result_args(desc, O, lse, workspace, dev_status, stream)), "bass_verify_attention_split")
 
 
 def bass_append_verify_attention(desc, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,

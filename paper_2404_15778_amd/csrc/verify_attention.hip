@@ -61,6 +61,8 @@ struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
   int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
   int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
+  int span;  // BASS-PAD variant: every active sequence is processed over at least this many cache
+             // positions (0: over its own length); the positions beyond its length are masked
   int fused_reduce;  // 1: the last-arriving wavefront merges a unit's partials; 0: a second launch does
   float scale_log2;  // scale * log2(e): scores are kept in the log2 domain
   const void* Q;
@@ -103,7 +105,9 @@ __device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bo
   L = p.ctx_len[b];
   nq = p.draft_len[b];
   bad = clamp_lengths(L, nq, p.kmax, p.Lcap);
-  return nq > 0 ? (L + nq + kBlockTokens - 1) / kBlockTokens : 0;
+  if (nq <= 0) return 0;
+  const int len = max(L + nq, min(p.span, p.Lcap));
+  return (len + kBlockTokens - 1) / kBlockTokens;
 }
 
 struct Unit {
@@ -1149,7 +1153,7 @@ static void read_pad_override() {
 static int launch_attention(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
                             const void* Kcache, const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
                             float* O, float* lse, void* workspace, size_t workspace_bytes, int32_t* dev_status,
-                            void* stream) {
+                            void* stream, int span = 0) {
   int rc = check_desc(d);
   if (rc != BASS_OK) return rc;
   if (!Q || !Kcache || !Vcache || !ctx_len || !draft_len || !O || !workspace) return BASS_ERR_INVALID_ARG;
@@ -1167,6 +1171,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(d->dtype == BASS_DTYPE_BF16 && rows_max > 16);
   p.pad = K_new ? g_append_pad : g_plain_pad;
+  p.span = span;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
   p.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || rows_max <= 16) ? 1 : 0;
   p.scale_log2 = d->scale * 1.4426950408889634f;
@@ -1217,6 +1222,39 @@ extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, con
                                      void* workspace, size_t workspace_bytes, int32_t* dev_status, void* stream) {
   return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
                                 workspace_bytes, dev_status, stream);
+}
+
+extern "C" int bass_verify_attention_pad(const bass_attn_desc* d, const void* Q, const void* Kcache,
+                                         const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                                         int32_t padded_len, float* O, float* lse, void* workspace,
+                                         size_t workspace_bytes, int32_t* dev_status, void* stream) {
+  if (padded_len < 0) return BASS_ERR_INVALID_ARG;
+  return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                workspace_bytes, dev_status, stream, padded_len);
+}
+
+extern "C" int bass_verify_attention_split(const bass_attn_desc* d, const void* Q, const void* Kcache,
+                                           const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                                           float* O, float* lse, void* workspace, size_t workspace_bytes,
+                                           int32_t* dev_status, void* stream) {
+  const int rc = bass::check_desc(d);
+  if (rc != BASS_OK) return rc;
+  if (!Q || !Kcache || !Vcache || !ctx_len || !draft_len || !O || !workspace) return BASS_ERR_INVALID_ARG;
+  if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  bass_attn_desc one = *d;
+  one.B = 1;
+  const size_t elt = d->dtype == BASS_DTYPE_BF16 ? 2 : 4;
+  const size_t q_seq = (size_t)d->kmax * d->Hq * d->D;  // elements of Q (and O) per sequence
+  const size_t cache_seq = bass_kv_cache_bytes(&one);
+  for (int b = 0; b < d->B; ++b) {  // one launch per sequence; they share the workspace in stream order
+    const int r = bass::launch_attention(&one, (const char*)Q + b * q_seq * elt, nullptr, nullptr,
+                                         (const char*)Kcache + b * cache_seq, (const char*)Vcache + b * cache_seq,
+                                         ctx_len + b, draft_len + b, O + b * q_seq,
+                                         lse ? lse + (size_t)b * d->kmax * d->Hq : nullptr, workspace, workspace_bytes,
+                                         dev_status, stream);
+    if (r != BASS_OK) return r;
+  }
+  return BASS_OK;
 }
 
 extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void* Q, const void* K_new,

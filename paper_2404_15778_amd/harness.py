@@ -9,7 +9,7 @@ import numpy as np
 import torch
 
 from . import (AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
-               bass_spec_accept, bass_verify_attention, make_desc)
+               bass_spec_accept, bass_verify_attention, bass_verify_attention_pad, bass_verify_attention_split, make_desc)
 
 
 def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
@@ -53,9 +53,18 @@ class DeviceAttention:
         bass_kv_gather(d, self.Kc, self.Vc, K, V, start, count, self.status)
         return K, V
 
-    def verify(self, Q, ctx_len, draft_len, want_lse=True):
-        bass_verify_attention(self.desc, Q, self.Kc, self.Vc, ctx_len, draft_len, self.O,
-                              self.lse if want_lse else None, self.ws, self.status)
+    def verify(self, Q, ctx_len, draft_len, want_lse=True, variant="ragged", padded_len=0):
+        """variant: "ragged" (one launch, true lengths), "pad" (BASS-PAD), "split" (BASS-SPLIT)."""
+        lse = self.lse if want_lse else None
+        if variant == "pad":
+            bass_verify_attention_pad(self.desc, Q, self.Kc, self.Vc, ctx_len, draft_len, padded_len, self.O, lse,
+                                      self.ws, self.status)
+        elif variant == "split":
+            bass_verify_attention_split(self.desc, Q, self.Kc, self.Vc, ctx_len, draft_len, self.O, lse, self.ws,
+                                        self.status)
+        else:
+            bass_verify_attention(self.desc, Q, self.Kc, self.Vc, ctx_len, draft_len, self.O, lse, self.ws,
+                                  self.status)
         return self.O, self.lse
 
     def append_verify(self, Q, K_new, V_new, ctx_len, draft_len, want_lse=True):

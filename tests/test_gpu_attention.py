@@ -149,3 +149,27 @@ def test_repeated_calls_share_one_workspace(hip):
     finally:
         bass.bass_set_attention_waves(0)
     assert int(da.status.item()) == 0
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+@pytest.mark.parametrize("variant", ["pad", "split"])
+def test_pad_and_split_launch_variants_match_the_oracle(hip, dtype, D, variant):
+    # Section 3.2: BASS-PAD (padded positions take part and get probability exactly 0) and BASS-SPLIT
+    # (one launch per sequence) compute the same ragged attention; the caches are poisoned with NaN
+    # beyond every sequence's valid range, which PAD reads
+    import torch
+    w = wl.make_attention("variants", 5, 8, 4, D, dtype, [30, 63, 0, 500, 129], [6, 3, 2, 5, 0], 13, kmax=6, Lcap=520)
+    Or, lser = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    _, _, _, da = hip.run_attention_workload(w, poison=True)
+    Q, ctx, nq = hip.to_device(w.Q), hip.i32(w.ctx_len), hip.i32(w.draft_len)
+    longest = int((w.ctx_len + w.draft_len).max())
+    for padded_len in ((longest, w.Lcap, 10) if variant == "pad" else (0,)):
+        da.O.fill_(float("nan"))
+        da.lse.fill_(float("nan"))
+        O, lse = da.verify(Q, ctx, nq, variant=variant, padded_len=padded_len)
+        torch.cuda.synchronize()
+        O, lse = hip.to_host(O), hip.to_host(lse)
+        assert int(da.status.item()) == 0
+        assert np.isfinite(O).all() and np.isfinite(lse).all()
+        assert np.abs(O - Or).max() <= TOL[dtype]
+        assert np.abs(lse - lser).max() <= TOL[dtype]
