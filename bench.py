@@ -189,6 +189,25 @@ def main():
     attn_us = 1e3 * float(np.mean(attn_ms))
     accept_us = 1e3 * float(np.mean(accept_ms))
 
+    # ---- side measurement (not part of the timed step): the logits front end that would make p and q ---
+    # temperature 0.2, top-p 0.95 as in the paper's experiments; B*(k+1) main rows and B*k draft rows
+    lt, ld = wl.make_logits(acc.B, acc.kmax, acc.V, args.seed, 3.0, 1.0)
+    lt, ld = harness.to_device(lt, dev), harness.to_device(ld, dev)
+    pw, qw = torch.empty_like(lt), torch.empty_like(ld)
+    warp_ms = []
+    reps = 10  # pairs per timed run, so that the launches queue up behind each other on the GPU
+    for _ in range(2):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            bass.bass_warp_probs(lt, 0.2, 0.95, pw, status)
+            bass.bass_warp_probs(ld, 0.2, 0.95, qw, status)
+        e1.record()
+        torch.cuda.synchronize()
+        warp_ms.append(e0.elapsed_time(e1) / reps)
+    warp_us = 1e3 * warp_ms[-1]
+    del lt, ld, pw, qw
+
     kv_bytes = w.kv_bytes  # per layer
     step_bytes = kv_bytes * NL
     value = step_bytes / (wall / args.steps) / 1e9
@@ -220,6 +239,7 @@ def main():
         "emitted_tokens_per_s": round(float((n_acc_host + 1).sum()) / (wall / args.steps), 1),
         "attention_call_us": round(attn_us, 2),
         "spec_accept_us": round(accept_us, 2),
+        "logit_warp_us": round(warp_us, 2),
         "roofline": {
             "kernel": "verify_attn_bf16<128,1> (append + streaming + split-context reduction, one launch)",
             "bound": "hbm",

@@ -190,6 +190,24 @@ int bass_spec_accept(int32_t B, int32_t kmax, int32_t V, const float* p, const f
                      int32_t* dev_status, void* stream);
 
 /*
+ * Logits front end: temperature, nucleus (top-p) filter and softmax, producing the probability
+ * rows p and q that bass_spec_accept consumes (the paper's experiments use temperature 0.2 and
+ * nucleus top-p 0.95: captions of the result tables in Section 4).
+ *   logits [R, V] fp32 (device)   R rows, e.g. B * (kmax + 1) main-model or B * kmax draft-model rows
+ *   probs  [R, V] fp32 (device)   out; may not alias logits
+ * Per row: e_i = 2^((z_i - max z) * log2(e) / temperature); the tokens are ordered by decreasing
+ * e_i, equal values by increasing token id; the shortest prefix whose mass reaches top_p of the
+ * total is kept (the token that crosses top_p included; top_p >= 1 keeps every token); probs is
+ * e_i / (kept mass) on kept tokens and 0 elsewhere.  Masses are compared as the integers
+ * floor(e_i * 2^40) against ceil(top_p * their sum), so the kept set and the normaliser do not
+ * depend on summation order and repeated calls give identical bits.  NaN logits get probability 0;
+ * a row without any finite logit is written as zeros and raises BASS_STATUS_ZERO_MASS.
+ * temperature > 0, top_p > 0, V <= 2^19; otherwise BASS_ERR_INVALID_ARG / BASS_ERR_UNSUPPORTED.
+ */
+int bass_warp_probs(int32_t R, int32_t V, const float* logits, float temperature, float top_p,
+                    float* probs, int32_t* dev_status, void* stream);
+
+/*
  * Draft-length heuristic (Algorithm 1 of the paper; HOST code, HOST pointers): picks the
  * uniform draft length of the next speculative step from the numbers of drafts the sequences
  * accepted in the last one.  If some sequence accepted all l_draft drafts the length grows by

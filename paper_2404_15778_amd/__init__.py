@@ -23,7 +23,7 @@ DTYPE_BF16, DTYPE_FP32 = 0, 1
 EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
     "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_verify_attention_pad",
-    "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept",
+    "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept", "bass_warp_probs",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
 )
 
@@ -84,6 +84,8 @@ def lib():
         L.bass_append_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_spec_accept.restype = ctypes.c_int
         L.bass_spec_accept.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_warp_probs.restype = ctypes.c_int
+        L.bass_warp_probs.argtypes = [i32, i32, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp]
         L.bass_draft_len_init.restype = None
         L.bass_draft_len_init.argtypes = [ctypes.POINTER(DraftLenState), i32]
         L.bass_next_draft_len.restype = i32
@@ -283,6 +285,22 @@ def bass_spec_accept(p, q, draft_tok, n_draft, u, n_accept, next_token, ctx_len=
         _dev(u, "u", f32, (B, kmax + 1)), _dev(n_accept, "n_accept", i32, (B,)),
         _dev(next_token, "next_token", i32, (B,)), _dev(ctx_len, "ctx_len", i32, (B,), optional=True),
         _dev(dev_status, "dev_status", i32, optional=True), _stream(stream)), "bass_spec_accept")
+
+
+def bass_warp_probs(logits, temperature, top_p, probs, dev_status=None, stream=None):
+    """logits [..., V] fp32 -> probs of the same shape (temperature, nucleus top-p, softmax)."""
+    torch = _torch()
+    if logits is None or logits.dim() < 1:
+        raise ValueError("logits must be [..., V]")
+    V = int(logits.shape[-1])
+    R = int(logits.numel() // max(V, 1))
+    shape = tuple(logits.shape)
+    lp, pp = _dev(logits, "logits", torch.float32, shape), _dev(probs, "probs", torch.float32, shape)
+    if lp.value == pp.value:
+        raise ValueError("probs may not alias logits")
+    _check(lib().bass_warp_probs(R, V, lp, ctypes.c_float(float(temperature)), ctypes.c_float(float(top_p)), pp,
+                                 _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)),
+           "bass_warp_probs")
 
 
 # ---- allocation helpers (plumbing; no arithmetic) ----------------------------------------------

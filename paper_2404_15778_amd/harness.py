@@ -8,7 +8,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
+from . import (bass_warp_probs, AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
                bass_spec_accept, bass_verify_attention, bass_verify_attention_pad, bass_verify_attention_split, make_desc)
 
 
@@ -115,3 +115,13 @@ def run_accept_workload(a, ctx_len=None, device="cuda"):
     torch.cuda.synchronize()
     out = (to_host(n_accept), to_host(next_token), int(status.item()))
     return out if ctx is None else out + (to_host(ctx),)
+
+
+def run_warp_probs(logits: np.ndarray, temperature, top_p, device="cuda"):
+    """bass_warp_probs on host logits [..., V]; returns (probs on the host, status)."""
+    lg = to_device(np.asarray(logits, np.float32), device)
+    probs = torch.full_like(lg, float("nan"))
+    status = torch.zeros(1, dtype=torch.int32, device=device)
+    bass_warp_probs(lg, temperature, top_p, probs, status)
+    torch.cuda.synchronize()
+    return to_host(probs), int(status.item())

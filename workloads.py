@@ -147,6 +147,19 @@ def softmax_f32(x: np.ndarray) -> np.ndarray:
     return (e / e.sum(axis=-1, keepdims=True, dtype=np.float32)).astype(np.float32)
 
 
+def make_logits(B, kmax, V, seed, sigma_target, sigma_noise=None):
+    """Raw logits of the acceptance recipes: main-model rows [B, kmax+1, V] ~ N(0, sigma_target^2) and
+    draft-model rows [B, kmax, V], independent with the same sigma (sigma_noise None) or the main
+    model's plus N(0, sigma_noise^2).  fp32.  Inputs of the logits front end (temperature, top-p)."""
+    rng = np.random.default_rng([seed, 0x106175])
+    lt = rng.standard_normal((B, kmax + 1, V), dtype=np.float32) * np.float32(sigma_target)
+    if sigma_noise is None:
+        ld = rng.standard_normal((B, kmax, V), dtype=np.float32) * np.float32(sigma_target)
+    else:
+        ld = lt[:, :kmax] + rng.standard_normal((B, kmax, V), dtype=np.float32) * np.float32(sigma_noise)
+    return lt, ld
+
+
 def make_accept(name, B, kmax, V, seed, sigma_target, sigma_noise=None, n_draft=None) -> AcceptWorkload:
     """p = softmax(target logits ~ N(0, sigma_target^2)); q = softmax of independent logits with the
     same sigma (sigma_noise None) or of target logits + N(0, sigma_noise^2); drafts x_i ~ q_i."""
