@@ -7,7 +7,8 @@ and this package never imports the product.
 `bass_oracle.c` holds the arithmetic (plain fp64 C loops); this file only
 compiles it with gcc and marshals numpy arrays into it.  `draft_length.py`
 holds the draft-length heuristic (Algorithm 1) as plain Python, `logit_warp.py`
-the logits front end (temperature, nucleus top-p, softmax) in numpy.
+the logits front end (temperature, nucleus top-p, softmax) in numpy, `kv_int8.py`
+the INT8 KV-cache quantizer in numpy.
 """
 from __future__ import annotations
 
