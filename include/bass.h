@@ -43,7 +43,12 @@ enum {
   BASS_STATUS_ZERO_MASS = 4         /* a probability row had no mass to sample from             */
 };
 
-enum { BASS_DTYPE_BF16 = 0, BASS_DTYPE_FP32 = 1 };
+/* BASS_DTYPE_INT8KV: Q, K_new, V_new are bf16; the caches hold INT8 codes with one fp32 scale per
+ * token and kv head (the paper's appendix: dynamic per-head and per-token quantization of keys and
+ * values).  Symmetric: amax = max_d |x_d|, code_d = rint(x_d * (127 / amax)) (one fp32 division, one
+ * fp32 product, round half to even), scale = amax / 127; a row of zeros has scale 0.  The attention
+ * runs over the represented values code * scale. */
+enum { BASS_DTYPE_BF16 = 0, BASS_DTYPE_FP32 = 1, BASS_DTYPE_INT8KV = 2 };
 
 /* Shape of one attention layer's verification call. */
 typedef struct bass_attn_desc {
@@ -51,9 +56,9 @@ typedef struct bass_attn_desc {
   int32_t kmax;   /* query-token slots per sequence (tensors are padded to kmax)                */
   int32_t Hq;     /* query heads                                                                */
   int32_t Hkv;    /* key/value heads, Hq % Hkv == 0 (query head h uses kv head h / (Hq/Hkv))     */
-  int32_t D;      /* head size: 64 or 128 for bf16; a multiple of 4 up to 256 for fp32           */
+  int32_t D;      /* head size: 64 or 128 for bf16 / int8 caches; a multiple of 4 up to 256 for fp32 */
   int32_t Lcap;   /* cache capacity in tokens per sequence                                      */
-  int32_t dtype;  /* BASS_DTYPE_*: element type of Q, K, V, K_new, V_new; O is always fp32       */
+  int32_t dtype;  /* BASS_DTYPE_*: element type of Q, K_new, V_new and of the caches; O is fp32  */
   float scale;    /* the 1/c of P = softmax(Q^T K / c) (Section 3.2); callers pass 1/sqrt(D)     */
 } bass_attn_desc;
 
@@ -89,8 +94,19 @@ int bass_kv_append(const bass_attn_desc* desc, void* Kcache, void* Vcache, const
                    int32_t* dev_status, void* stream);
 
 /*
+ * INT8 caches only (desc->dtype == BASS_DTYPE_INT8KV): read the codes and scales of tokens
+ * start[b] .. start[b]+n[b]-1 back in token-major order.
+ *   K_codes, V_codes   [B, kmax, Hkv, D] int8 out
+ *   K_scales, V_scales [B, kmax, Hkv] fp32 out
+ * Rows beyond n[b] are left untouched.
+ */
+int bass_kv_gather_int8(const bass_attn_desc* desc, const void* Kcache, const void* Vcache,
+                        int8_t* K_codes, int8_t* V_codes, float* K_scales, float* V_scales,
+                        const int32_t* start, const int32_t* n, int32_t* dev_status, void* stream);
+
+/*
  * Read cache rows back in token-major order (inverse of bass_kv_append; for tests and for
- * moving a sequence): K_out, V_out [B, kmax, Hkv, D] receive tokens
+ * moving a sequence; bf16 and fp32 caches): K_out, V_out [B, kmax, Hkv, D] receive tokens
  * start[b] .. start[b]+n[b]-1 of sequence b; other rows are left untouched.
  */
 int bass_kv_gather(const bass_attn_desc* desc, const void* Kcache, const void* Vcache, void* K_out,

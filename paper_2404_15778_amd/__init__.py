@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libbass.so")
 OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = -1, -2, -3, -4
 STATUS_LEN_CLAMPED, STATUS_TOKEN_CLAMPED, STATUS_ZERO_MASS = 1, 2, 4
-DTYPE_BF16, DTYPE_FP32 = 0, 1
+DTYPE_BF16, DTYPE_FP32, DTYPE_INT8KV = 0, 1, 2
 
 # every symbol include/bass.h declares
 EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
-    "bass_kv_append", "bass_kv_gather", "bass_verify_attention", "bass_verify_attention_pad",
+    "bass_kv_append", "bass_kv_gather", "bass_kv_gather_int8", "bass_verify_attention", "bass_verify_attention_pad",
     "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept", "bass_warp_probs",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
 )
@@ -74,6 +74,8 @@ def lib():
         L.bass_kv_append.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_kv_gather.restype = ctypes.c_int
         L.bass_kv_gather.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bass_kv_gather_int8.restype = ctypes.c_int
+        L.bass_kv_gather_int8.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_verify_attention.restype = ctypes.c_int
         L.bass_verify_attention.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.bass_verify_attention_pad.restype = ctypes.c_int
@@ -124,7 +126,7 @@ def bass_next_draft_len(state: DraftLenState, n_accept, l_incre: int = 0, l_mod:
 
 
 def make_desc(B, kmax, Hq, Hkv, D, Lcap, dtype, scale) -> AttnDesc:
-    code = {"bf16": DTYPE_BF16, "fp32": DTYPE_FP32}.get(dtype, dtype)
+    code = {"bf16": DTYPE_BF16, "fp32": DTYPE_FP32, "int8kv": DTYPE_INT8KV}.get(dtype, dtype)
     return AttnDesc(int(B), int(kmax), int(Hq), int(Hkv), int(D), int(Lcap), int(code), float(scale))
 
 
@@ -145,7 +147,7 @@ def _torch():
 
 def _elt_dtype(desc):
     torch = _torch()
-    return torch.bfloat16 if desc.dtype == DTYPE_BF16 else torch.float32
+    return torch.float32 if desc.dtype == DTYPE_FP32 else torch.bfloat16  # INT8 caches: Q and new rows are bf16
 
 
 def _dev(t, name, dtype=None, shape=None, optional=False):
@@ -206,6 +208,18 @@ def bass_kv_gather(desc, Kcache, Vcache, K_out, V_out, start, n, dev_status=None
         _dev(K_out, "K_out", et, rows), _dev(V_out, "V_out", et, rows),
         _dev(start, "start", torch.int32, (desc.B,)), _dev(n, "n", torch.int32, (desc.B,)),
         _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_kv_gather")
+
+
+def bass_kv_gather_int8(desc, Kcache, Vcache, K_codes, V_codes, K_scales, V_scales, start, n, dev_status=None,
+                        stream=None):
+    torch = _torch()
+    rows = (desc.B, desc.kmax, desc.Hkv, desc.D)
+    _check(lib().bass_kv_gather_int8(
+        ctypes.byref(desc), _cache_ptr(Kcache, desc, "Kcache"), _cache_ptr(Vcache, desc, "Vcache"),
+        _dev(K_codes, "K_codes", torch.int8, rows), _dev(V_codes, "V_codes", torch.int8, rows),
+        _dev(K_scales, "K_scales", torch.float32, rows[:3]), _dev(V_scales, "V_scales", torch.float32, rows[:3]),
+        _dev(start, "start", torch.int32, (desc.B,)), _dev(n, "n", torch.int32, (desc.B,)),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_kv_gather_int8")
 
 
 def bass_verify_attention(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace, dev_status=None,

@@ -43,6 +43,30 @@ __host__ __device__ inline size_t v_elem_offset(int /*D*/, int tok_in_blk, int d
   return (size_t)((mt * 64 + grp * 16 + dr) * 8 + j);
 }
 
+// ---------------------------------------------------------------------------------------
+// INT8 cache layout (BASS_DTYPE_INT8KV).  Same blocks of 32 tokens; a block holds the 32*D codes
+// in the element order of the bf16 layout above -- fragment f (K: f = tt*(D/32) + t, V: f = mt) of a
+// lane is 8 codes = 8 bytes -- with two consecutive fragments packed into a lane's 16-byte chunk so
+// that a wavefront still reads 1 KiB per load instruction:
+//   byte offset of code j of fragment f of a lane = ((f/2)*64 + lane)*16 + (f%2)*8 + j
+// followed by the block's 32 fp32 scales in token order (one per token of this kv head).
+// ---------------------------------------------------------------------------------------
+__host__ __device__ inline size_t i8_block_bytes(int D) { return (size_t)kBlockTokens * D + kBlockTokens * 4; }
+
+__host__ __device__ inline size_t i8_k_offset(int D, int tok_in_blk, int d) {
+  const int tt = tok_in_blk >> 4, r = tok_in_blk & 15;
+  const int t = d >> 5, grp = (d & 31) >> 3, j = d & 7;
+  const int f = tt * (D >> 5) + t, lane = grp * 16 + r;
+  return (size_t)(((f >> 1) * 64 + lane) * 16 + (f & 1) * 8 + j);
+}
+
+__host__ __device__ inline size_t i8_v_offset(int /*D*/, int tok_in_blk, int d) {
+  const int half = tok_in_blk >> 4, w = tok_in_blk & 15;
+  const int grp = w >> 2, j = half * 4 + (w & 3);
+  const int f = d >> 4, lane = grp * 16 + (d & 15);
+  return (size_t)(((f >> 1) * 64 + lane) * 16 + (f & 1) * 8 + j);
+}
+
 // Per-sequence lengths with the clamping the header promises.  L = cached tokens before the
 // step, nq = query tokens; on return 0 <= nq <= kmax, 0 <= L, L + nq <= Lcap.
 __device__ inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {
@@ -60,7 +84,7 @@ inline int check_desc(const bass_attn_desc* d) {
   if (d->B <= 0 || d->kmax <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->D <= 0 || d->Lcap <= 0)
     return BASS_ERR_INVALID_ARG;
   if (d->Hq % d->Hkv != 0) return BASS_ERR_INVALID_ARG;
-  if (d->dtype == BASS_DTYPE_BF16) {
+  if (d->dtype == BASS_DTYPE_BF16 || d->dtype == BASS_DTYPE_INT8KV) {
     if (d->D != 64 && d->D != 128) return BASS_ERR_UNSUPPORTED;
   } else if (d->dtype == BASS_DTYPE_FP32) {
     if (d->D % 4 != 0 || d->D > 256) return BASS_ERR_UNSUPPORTED;

@@ -6,7 +6,9 @@
 //
 // The library owns the cache layout: bf16 caches are kept in MFMA fragment order (see
 // bass_common.h) so the attention kernel's loads are 1 KiB-contiguous per wavefront and
-// need no transposition; fp32 caches are token-major [B][Hkv][Lcap][D].
+// need no transposition; fp32 caches are token-major [B][Hkv][Lcap][D]; INT8 caches (the paper's
+// appendix: keys and values quantized dynamically per head and per token) hold codes in the same
+// fragment order plus one fp32 scale per token and kv head.
 #include "bass_common.h"
 
 namespace bass {
@@ -20,6 +22,8 @@ struct KvParams {
   const int32_t* off;  // [B] first cache token
   const int32_t* cnt;  // [B] number of rows
   int32_t* status;
+  float* Ks;  // INT8 gather only: scales out [B,kmax,Hkv]
+  float* Vs;
 };
 
 // One thread per (sequence b, row slot i, kv head, 16-byte chunk of the row): everything a thread
@@ -97,19 +101,118 @@ __global__ __launch_bounds__(256) void kv_rows_fp32(KvParams p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// INT8 caches.  One thread per (sequence, row slot, kv head, chunk of 8 head elements); the D/8
+// threads of a row are consecutive lanes of one wavefront and agree on the row's largest
+// magnitude through shuffles, so no thread may leave before them.
+// ---------------------------------------------------------------------------------------
+__device__ inline float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// codes of 8 bf16 values (in a uint4) for the row scale 127 / amax; returns them packed in 8 bytes
+__device__ inline uint2 quantize8(const uint4& v, float inv) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  uint32_t out[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float x = bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+    const int code = (int)__builtin_rintf(x * inv);  // one fp32 product, round half to even
+    out[e >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (e & 3));
+  }
+  return make_uint2(out[0], out[1]);
+}
+
+__device__ inline float amax8(const uint4& v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float m = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu)));
+  return m;
+}
+
+__global__ __launch_bounds__(256) void kv_rows_i8_append(KvParams p) {
+  const int chunks = p.D / 8;  // 8 or 16: a row's threads share an aligned group of lanes
+  const long total = (long)p.B * p.kmax * p.Hkv * chunks;
+  const long item_raw = (long)blockIdx.x * 256 + threadIdx.x;  // over [B][kmax][Hkv][chunks]
+  const bool in_range = item_raw < total;
+  const long item = in_range ? item_raw : total - 1;
+  const int ck = (int)(item % chunks);
+  const int kvh = (int)((item / chunks) % p.Hkv);
+  const int i = (int)((item / ((long)chunks * p.Hkv)) % p.kmax);
+  const int b = (int)(item / ((long)chunks * p.Hkv * p.kmax));
+  long tok = 0;
+  const bool ok = in_range && row_target(p, b, i, ck == 0 && kvh == 0, tok);
+  uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
+  if (ok) {
+    kv = *(const uint4*)((const uint16_t*)p.Kr + (size_t)item * 8);
+    vv = *(const uint4*)((const uint16_t*)p.Vr + (size_t)item * 8);
+  }
+  float ka = amax8(kv), va = amax8(vv);
+  for (int o = chunks >> 1; o >= 1; o >>= 1) {
+    ka = fmaxf(ka, __shfl_xor(ka, o));
+    va = fmaxf(va, __shfl_xor(va, o));
+  }
+  if (!ok) return;
+  const float kinv = ka > 0.f ? 127.0f / ka : 0.f;  // one fp32 division each
+  const float vinv = va > 0.f ? 127.0f / va : 0.f;
+  const int blk = (int)(tok / kBlockTokens), w = (int)(tok % kBlockTokens);
+  const size_t base = (((size_t)b * p.Hkv + kvh) * p.nblk + blk) * i8_block_bytes(p.D);
+  uint8_t* kc = (uint8_t*)p.Kc + base;
+  uint8_t* vc = (uint8_t*)p.Vc + base;
+  *(uint2*)(kc + i8_k_offset(p.D, w, ck * 8)) = quantize8(kv, kinv);  // 8 consecutive d share 8 bytes
+  const uint2 vq = quantize8(vv, vinv);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) vc[i8_v_offset(p.D, w, ck * 8 + e)] = (uint8_t)((e < 4 ? vq.x : vq.y) >> (8 * (e & 3)));
+  if (ck == 0) {
+    ((float*)(kc + (size_t)kBlockTokens * p.D))[w] = ka / 127.0f;
+    ((float*)(vc + (size_t)kBlockTokens * p.D))[w] = va / 127.0f;
+  }
+}
+
+__global__ __launch_bounds__(256) void kv_rows_i8_gather(KvParams p) {
+  const int chunks = p.D / 8;
+  const long item = (long)blockIdx.x * 256 + threadIdx.x;  // over [B][kmax][Hkv][chunks]
+  if (item >= (long)p.B * p.kmax * p.Hkv * chunks) return;
+  const int ck = (int)(item % chunks);
+  const int kvh = (int)((item / chunks) % p.Hkv);
+  const int i = (int)((item / ((long)chunks * p.Hkv)) % p.kmax);
+  const int b = (int)(item / ((long)chunks * p.Hkv * p.kmax));
+  long tok;
+  if (!row_target(p, b, i, ck == 0 && kvh == 0, tok)) return;
+  const int blk = (int)(tok / kBlockTokens), w = (int)(tok % kBlockTokens);
+  const size_t base = (((size_t)b * p.Hkv + kvh) * p.nblk + blk) * i8_block_bytes(p.D);
+  const uint8_t* kc = (const uint8_t*)p.Kc + base;
+  const uint8_t* vc = (const uint8_t*)p.Vc + base;
+  *(uint2*)((uint8_t*)p.Kr + (size_t)item * 8) = *(const uint2*)(kc + i8_k_offset(p.D, w, ck * 8));
+  uint32_t out[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e >> 2] |= (uint32_t)vc[i8_v_offset(p.D, w, ck * 8 + e)] << (8 * (e & 3));
+  *(uint2*)((uint8_t*)p.Vr + (size_t)item * 8) = make_uint2(out[0], out[1]);
+  if (ck == 0) {
+    const size_t row = item / chunks;  // [B][kmax][Hkv]
+    p.Ks[row] = ((const float*)(kc + (size_t)kBlockTokens * p.D))[w];
+    p.Vs[row] = ((const float*)(vc + (size_t)kBlockTokens * p.D))[w];
+  }
+}
+
 template <bool kGather>
 static int launch_rows(const bass_attn_desc* d, void* Kc, void* Vc, void* Kr, void* Vr, const int32_t* off,
-                       const int32_t* cnt, int32_t* status, void* stream) {
+                       const int32_t* cnt, int32_t* status, void* stream, float* Ks = nullptr, float* Vs = nullptr) {
   int rc = check_desc(d);
   if (rc != BASS_OK) return rc;
   if (!Kc || !Vc || !Kr || !Vr || !off || !cnt) return BASS_ERR_INVALID_ARG;
-  const int chunk = d->dtype == BASS_DTYPE_BF16 ? 8 : 4;
+  if (d->dtype == BASS_DTYPE_INT8KV && (kGather != (Ks != nullptr) || kGather != (Vs != nullptr)))
+    return BASS_ERR_UNSUPPORTED;  // INT8 caches are read back with bass_kv_gather_int8
+  if (d->dtype != BASS_DTYPE_INT8KV && Ks) return BASS_ERR_UNSUPPORTED;
+  const int chunk = d->dtype == BASS_DTYPE_FP32 ? 4 : 8;
   const int64_t items = (int64_t)d->B * d->kmax * d->Hkv * (d->D / chunk);
   if ((items + 255) / 256 > 0x7fffffff) return BASS_ERR_UNSUPPORTED;
-  KvParams p{d->B, d->kmax, d->Hkv, d->D, d->Lcap, num_blocks(d->Lcap), Kc, Vc, Kr, Vr, off, cnt, status};
+  KvParams p{d->B, d->kmax, d->Hkv, d->D, d->Lcap, num_blocks(d->Lcap), Kc, Vc, Kr, Vr, off, cnt, status, Ks, Vs};
   dim3 grid((unsigned)((items + 255) / 256));
   hipStream_t s = (hipStream_t)stream;
-  if (d->dtype == BASS_DTYPE_BF16)
+  if (d->dtype == BASS_DTYPE_INT8KV) {
+    if (kGather) hipLaunchKernelGGL(kv_rows_i8_gather, grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(kv_rows_i8_append, grid, dim3(256), 0, s, p);
+  } else if (d->dtype == BASS_DTYPE_BF16)
     hipLaunchKernelGGL(kv_rows_bf16<kGather>, grid, dim3(256), 0, s, p);
   else
     hipLaunchKernelGGL(kv_rows_fp32<kGather>, grid, dim3(256), 0, s, p);
@@ -120,6 +223,8 @@ static int launch_rows(const bass_attn_desc* d, void* Kc, void* Vc, void* Kr, vo
 
 extern "C" size_t bass_kv_cache_bytes(const bass_attn_desc* d) {
   if (bass::check_desc(d) != BASS_OK) return 0;
+  if (d->dtype == BASS_DTYPE_INT8KV)
+    return (size_t)d->B * d->Hkv * bass::num_blocks(d->Lcap) * bass::i8_block_bytes(d->D);
   if (d->dtype == BASS_DTYPE_BF16)
     return (size_t)d->B * d->Hkv * bass::num_blocks(d->Lcap) * bass::kBlockTokens * d->D * 2;
   return (size_t)d->B * d->Hkv * d->Lcap * d->D * 4;
@@ -137,4 +242,13 @@ extern "C" int bass_kv_gather(const bass_attn_desc* desc, const void* Kcache, co
                               void* stream) {
   return bass::launch_rows<true>(desc, (void*)Kcache, (void*)Vcache, K_out, V_out, start, n, dev_status,
                                  stream);
+}
+
+extern "C" int bass_kv_gather_int8(const bass_attn_desc* desc, const void* Kcache, const void* Vcache,
+                                   int8_t* K_codes, int8_t* V_codes, float* K_scales, float* V_scales,
+                                   const int32_t* start, const int32_t* n, int32_t* dev_status, void* stream) {
+  if (!desc || desc->dtype != BASS_DTYPE_INT8KV) return desc ? BASS_ERR_UNSUPPORTED : BASS_ERR_INVALID_ARG;
+  if (!K_scales || !V_scales) return BASS_ERR_INVALID_ARG;
+  return bass::launch_rows<true>(desc, (void*)Kcache, (void*)Vcache, K_codes, V_codes, start, n, dev_status, stream,
+                                 K_scales, V_scales);
 }

@@ -27,6 +27,7 @@
 // stored in that token order, so P goes from accumulator to operand with a bf16 pack only.
 // Query rows of one kv head are (draft i, head-in-group) pairs, up to 64 rows = 4 tiles.
 #include <cstdio>
+#include <type_traits>
 #include <cstdlib>
 
 #include "bass_common.h"
@@ -482,6 +483,57 @@ __device__ inline void load_block(KvRegs<D>& r, const uint4* kb, const uint4* vb
   for (int i = 0; i < D / 16; ++i) r.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(vb + i * 64)));
 }
 
+// Scales of the eight tokens whose scores / probabilities a lane holds (INT8 caches): slot j is token
+// 4 grp + j (j < 4) or 16 + 4 grp + j - 4 of the block.
+struct TokenScales {
+  float k[8], v[8];
+};
+
+// INT8 caches: a block's codes (two fragments per 16-byte chunk) and the scales of this lane's tokens.
+template <int D>
+struct KvRegsI8 {
+  u32x4 k[D / 32], v[D / 32];
+  f32x4 ks[2], vs[2];  // tokens 4 grp .. 4 grp + 3 and 16 + 4 grp .. 16 + 4 grp + 3
+};
+
+// kb, vb: the block's first uint4; lane16 / grp16 are this lane's offsets (0 for a dummy fetch)
+template <int D>
+__device__ inline void load_block_i8(KvRegsI8<D>& r, const uint4* kb, const uint4* vb, int lane16, int grp16) {
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) r.k[i] = __builtin_nontemporal_load((const u32x4*)(kb + i * 64 + lane16));
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4*)(vb + i * 64 + lane16));
+  const f32x4* ks = (const f32x4*)(kb + 2 * D);  // the codes take 32 D bytes = 2 D uint4
+  const f32x4* vs = (const f32x4*)(vb + 2 * D);
+  r.ks[0] = ks[grp16];
+  r.ks[1] = ks[4 + grp16];
+  r.vs[0] = vs[grp16];
+  r.vs[1] = vs[4 + grp16];
+}
+
+// eight INT8 codes (two words) -> eight bf16 (exact: |code| <= 127)
+__device__ inline uint4 codes_to_bf16(uint32_t lo, uint32_t hi) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)(float)(int)(int8_t)((e < 4 ? lo : hi) >> (8 * (e & 3)));
+  return __builtin_bit_cast(uint4, o);
+}
+
+template <int D>
+__device__ inline void dequant_block(const KvRegsI8<D>& q, KvRegs<D>& r, TokenScales& sc) {
+#pragma unroll
+  for (int f = 0; f < 2 * (D / 32); ++f) r.k[f] = codes_to_bf16(q.k[f >> 1][2 * (f & 1)], q.k[f >> 1][2 * (f & 1) + 1]);
+#pragma unroll
+  for (int f = 0; f < D / 16; ++f) r.v[f] = codes_to_bf16(q.v[f >> 1][2 * (f & 1)], q.v[f >> 1][2 * (f & 1) + 1]);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    sc.k[j] = q.ks[0][j];
+    sc.k[4 + j] = q.ks[1][j];
+    sc.v[j] = q.vs[0][j];
+    sc.v[4 + j] = q.vs[1][j];
+  }
+}
+
 // Fused append: the step's own K/V rows of one unit (rows i < nq of K_new, V_new for sequence b,
 // kv head kvh).  The wavefront whose share holds the unit's last blocks copies those rows into its
 // own slice of LDS before it starts streaming; when it reaches the (masked) blocks the new tokens
@@ -552,13 +604,24 @@ struct RowState {
 
 // One 32-token block against all query tiles.  kMasked: the block reaches beyond ctx_len, so
 // causal limits and the valid-token bound apply (wave-uniform choice).
-template <int D, int NT, bool kMasked>
+template <int D, int NT, bool kMasked, bool kI8 = false>
 __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int tok0,
                                   int n_valid, const int (&lim)[NT], float scale_log2, int lane,
                                   bool fused = false, const NewRows& nr = NewRows{}, uint4* kdst = nullptr,
-                                  uint4* vdst = nullptr) {
+                                  uint4* vdst = nullptr, const TokenScales* sc = nullptr) {
   constexpr int KS = D / 32, MT = D / 16;
   const int grp = lane >> 4;
+  // INT8 caches: r holds the codes as bf16; a score is (q . codes) * k-scale, a value code * v-scale,
+  // the latter folded into the probabilities that multiply V.  Stale tokens may carry any scale.
+  float ksl[8], vsl[8];
+  if (kI8) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      ksl[j] = sc->k[j] * scale_log2;
+      vsl[j] = sc->v[j];
+      if (kMasked && tok0 + (j < 4 ? 4 * grp + j : 16 + 4 * grp + (j - 4)) >= n_valid) vsl[j] = 0.f;
+    }
+  }
   bool v_new = false;  // this lane's V chunks hold a new token
   if (kMasked && fused) {
     const int dr = lane & 15;
@@ -623,8 +686,8 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     float s[8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      s[j] = s0[j] * scale_log2;
-      s[4 + j] = s1[j] * scale_log2;
+      s[j] = s0[j] * (kI8 ? ksl[j] : scale_log2);
+      s[4 + j] = s1[j] * (kI8 ? ksl[4 + j] : scale_log2);
     }
     if (kMasked) {
 #pragma unroll
@@ -647,7 +710,7 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     for (int j = 0; j < 8; ++j) {
       const float pj = __builtin_amdgcn_exp2f(s[j] - m_use);
       psum += pj;
-      pf[j] = (__bf16)pj;
+      pf[j] = (__bf16)(kI8 ? pj * vsl[j] : pj);
     }
     st.l[nt] = st.l[nt] * alpha + psum;
     st.m[nt] = m_new;
@@ -657,17 +720,18 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
   }
 }
 
-template <int D, int NT>
+template <int D, int NT, bool kI8 = false>
 __device__ inline void block_dispatch(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int blk,
                                       int L, int n_valid, const int (&lim)[NT], float scale_log2, int lane,
-                                      bool fused, const NewRows& nr, uint4* kdst, uint4* vdst) {
+                                      bool fused, const NewRows& nr, uint4* kdst, uint4* vdst,
+                                      const TokenScales* sc = nullptr) {
   const int tok0 = blk * kBlockTokens;
   // plain step: every token of the block is visible to every query (tokens <= L) and, with a fused
   // append, none of them is new (tokens < L)
   if (tok0 + kBlockTokens - 1 < L + (fused ? 0 : 1))
-    block_step<D, NT, false>(r, qf, st, tok0, n_valid, lim, scale_log2, lane);
+    block_step<D, NT, false, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, false, NewRows{}, nullptr, nullptr, sc);
   else
-    block_step<D, NT, true>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, fused, nr, kdst, vdst);
+    block_step<D, NT, true, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, fused, nr, kdst, vdst, sc);
 }
 
 // fp32 path: the wavefront whose share holds the new rows copies them into the (token-major) cache
@@ -747,9 +811,11 @@ __device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, 
   }
 }
 
-template <int D, int NT>
+template <int D, int NT, bool kI8 = false>
 __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
-  constexpr ptrdiff_t kBlkVec = (ptrdiff_t)kBlockTokens * D * 2 / 16;  // uint4 per block
+  // uint4 per block: 32 tokens of D bf16, or of D INT8 codes followed by 32 fp32 scales
+  constexpr ptrdiff_t kBlkVec = kI8 ? 2 * D + 8 : (ptrdiff_t)kBlockTokens * D * 2 / 16;
+  using Regs = typename std::conditional<kI8, KvRegsI8<D>, KvRegs<D>>::type;
   // With one query tile there are registers to spare for a second unit's state, so a wavefront
   // whose share of blocks crosses a unit boundary keeps streaming: it parks the first unit's
   // accumulators, carries on with the second unit, and delivers both partials at the end.
@@ -839,12 +905,18 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     // exact (a fetch under a branch would force a wait for ALL outstanding loads at the join and
     // serialise load and compute).  A fetch past the end of the share reads 16 bytes of the
     // share's first block with every lane instead: valid memory, one cache line, never used.
-    auto fetch = [&](KvRegs<D>& r, int s) {
-      ptrdiff_t off = vecA;
-      if (s < n) off = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec + lane;
-      load_block<D>(r, kc + off, vc + off);
+    auto fetch = [&](Regs& r, int s) {
+      if constexpr (kI8) {
+        const bool real = s < n;
+        const ptrdiff_t off = real ? (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec : vecA;
+        load_block_i8<D>(r, kc + off, vc + off, real ? lane : 0, real ? grp : 0);
+      } else {
+        ptrdiff_t off = vecA;
+        if (s < n) off = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec + lane;
+        load_block<D>(r, kc + off, vc + off);
+      }
     };
-    auto step = [&](KvRegs<D>& r, int s) {
+    auto step = [&](Regs& r, int s) {
       if constexpr (kPair) {
         if (s == nA) {  // first block of unit B: park A's state (register moves only)
           parked = st;
@@ -865,12 +937,20 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       for (int i = 0; i < D / 16; ++i) xx ^= r.v[i].x ^ r.v[i].y ^ r.v[i].z ^ r.v[i].w;
       st.l[0] += __uint_as_float(xx & 0x3f800000u);
 #else
-      block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
+      if constexpr (kI8) {
+        KvRegs<D> t;
+        TokenScales sc;
+        dequant_block<D>(r, t, sc);
+        block_dispatch<D, NT, true>(t, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, false,
+                                    cur_new, nullptr, nullptr, &sc);
+      } else {
+        block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
+      }
 #endif
     };
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
-      KvRegs<D> r0, r1, r2;
+      Regs r0, r1, r2;
       fetch(r0, 0);
       fetch(r1, 1);
       if (stage1) {
@@ -887,7 +967,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       }
     } else {
       // many query rows need the registers for accumulators: two-deep ring
-      KvRegs<D> r0, r1;
+      Regs r0, r1;
       fetch(r0, 0);
       if (stage1) {
         stage_commit<D>(u1, 0, lane, sr, new1);
@@ -1161,7 +1241,9 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   if (((uintptr_t)workspace & 15) != 0) return BASS_ERR_INVALID_ARG;
   const int g = d->Hq / d->Hkv;
   const int rows_max = d->kmax * g;
-  if (d->dtype == BASS_DTYPE_BF16 && rows_max > 64) return BASS_ERR_UNSUPPORTED;
+  const bool mfma = d->dtype != BASS_DTYPE_FP32;  // bf16 or INT8 caches: the matrix-core kernel
+  if (mfma && rows_max > 64) return BASS_ERR_UNSUPPORTED;
+  if (d->dtype == BASS_DTYPE_INT8KV && K_new) return BASS_ERR_UNSUPPORTED;  // appended by a launch of its own
   // partials of one unit are addressed with 32-bit byte offsets
   if ((int64_t)rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
   if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
@@ -1169,7 +1251,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   read_pad_override();
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
-  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(d->dtype == BASS_DTYPE_BF16 && rows_max > 16);
+  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16);
   p.pad = K_new ? g_append_pad : g_plain_pad;
   p.span = span;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
@@ -1196,13 +1278,23 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
     // LDS slice per wavefront of a fused append: K and V rows of two units
     const size_t lds = K_new ? (size_t)p.wpw * 4 * d->kmax * d->D * 2 : 0;
 #define BASS_LAUNCH(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN>), grid, block, lds, s, p)
-    if (d->D == 128) {
+#define BASS_LAUNCH_I8(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN, true>), grid, block, 0, s, p)
+    if (d->dtype == BASS_DTYPE_INT8KV) {
+      if (d->D == 128) {
+        if (nt == 1) BASS_LAUNCH_I8(128, 1); else if (nt == 2) BASS_LAUNCH_I8(128, 2);
+        else if (nt == 3) BASS_LAUNCH_I8(128, 3); else BASS_LAUNCH_I8(128, 4);
+      } else {
+        if (nt == 1) BASS_LAUNCH_I8(64, 1); else if (nt == 2) BASS_LAUNCH_I8(64, 2);
+        else if (nt == 3) BASS_LAUNCH_I8(64, 3); else BASS_LAUNCH_I8(64, 4);
+      }
+    } else if (d->D == 128) {
       if (nt == 1) BASS_LAUNCH(128, 1); else if (nt == 2) BASS_LAUNCH(128, 2);
       else if (nt == 3) BASS_LAUNCH(128, 3); else BASS_LAUNCH(128, 4);
     } else {
       if (nt == 1) BASS_LAUNCH(64, 1); else if (nt == 2) BASS_LAUNCH(64, 2);
       else if (nt == 3) BASS_LAUNCH(64, 3); else BASS_LAUNCH(64, 4);
     }
+#undef BASS_LAUNCH_I8
 #undef BASS_LAUNCH
   }
   if (launch_status() != BASS_OK) return BASS_ERR_HIP;
@@ -1243,7 +1335,7 @@ extern "C" int bass_verify_attention_split(const bass_attn_desc* d, const void* 
   if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
   bass_attn_desc one = *d;
   one.B = 1;
-  const size_t elt = d->dtype == BASS_DTYPE_BF16 ? 2 : 4;
+  const size_t elt = d->dtype == BASS_DTYPE_FP32 ? 4 : 2;  // Q is bf16 with bf16 and with INT8 caches
   const size_t q_seq = (size_t)d->kmax * d->Hq * d->D;  // elements of Q (and O) per sequence
   const size_t cache_seq = bass_kv_cache_bytes(&one);
   for (int b = 0; b < d->B; ++b) {  // one launch per sequence; they share the workspace in stream order
@@ -1262,8 +1354,10 @@ extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void*
                                             const int32_t* draft_len, float* O, float* lse, void* workspace,
                                             size_t workspace_bytes, int32_t* dev_status, void* stream) {
   if (!K_new || !V_new) return BASS_ERR_INVALID_ARG;
-  if (d && d->dtype == BASS_DTYPE_BF16 && (int64_t)d->kmax * d->D > bass::kMaxStagedElems) {
-    // more new rows than a wavefront stages in LDS: append with a launch of its own
+  if (d && (d->dtype == BASS_DTYPE_INT8KV ||
+            (d->dtype == BASS_DTYPE_BF16 && (int64_t)d->kmax * d->D > bass::kMaxStagedElems))) {
+    // INT8 caches (rows are quantized by the append kernel), or more new rows than a wavefront stages
+    // in LDS: append with a launch of its own
     const int rc = bass_kv_append(d, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, dev_status, stream);
     if (rc != BASS_OK) return rc;
     return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,

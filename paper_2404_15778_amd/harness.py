@@ -8,7 +8,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (bass_warp_probs, AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
+from . import (bass_kv_gather_int8, bass_warp_probs, AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
                bass_spec_accept, bass_verify_attention, bass_verify_attention_pad, bass_verify_attention_split, make_desc)
 
 
@@ -44,6 +44,16 @@ class DeviceAttention:
         """Write rows [B, n, Hkv, D] (torch, on device) at per-sequence offsets."""
         d = self.desc.replace(kmax=int(K_rows.shape[1]))
         bass_kv_append(d, self.Kc, self.Vc, K_rows, V_rows, offset, count, self.status)
+
+    def gather_int8(self, start, count, n):
+        """INT8 caches: (K codes, V codes, K scales, V scales) of tokens start .. start + count - 1."""
+        d = self.desc.replace(kmax=int(n))
+        Kq = torch.zeros((d.B, n, d.Hkv, d.D), dtype=torch.int8, device=self.device)
+        Vq = torch.zeros_like(Kq)
+        Ks = torch.zeros((d.B, n, d.Hkv), dtype=torch.float32, device=self.device)
+        Vs = torch.zeros_like(Ks)
+        bass_kv_gather_int8(d, self.Kc, self.Vc, Kq, Vq, Ks, Vs, start, count, self.status)
+        return Kq, Vq, Ks, Vs
 
     def gather(self, start, count, n):
         d = self.desc.replace(kmax=int(n))

@@ -1,0 +1,121 @@
+"""GPU parity of the INT8 KV cache: codes and scales bit for bit against the quantizer oracle, attention
+over the INT8 cache against the fp64 attention oracle run on the represented values code * scale."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from oracle.kv_int8 import dequantize_rows, quantize_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2   # same bar as the bf16 path: P is rounded to bf16 before the matrix cores in both
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2404_15778_amd import harness
+    return harness
+
+
+def reference(w):
+    """Oracle codes/scales of the whole logical cache and the attention over the represented values."""
+    Kf, Vf = wl.bf16_bits_to_f32(w.K), wl.bf16_bits_to_f32(w.V)
+    Kq, Ks = quantize_rows(Kf)
+    Vq, Vs = quantize_rows(Vf)
+    O, lse = oracle.verify_attention(wl.bf16_bits_to_f32(w.Q), dequantize_rows(Kq, Ks), dequantize_rows(Vq, Vs),
+                                     w.ctx_len, w.draft_len, w.scale)
+    return (Kq, Ks, Vq, Vs), O, lse
+
+
+def run(hip, w, two_step=True, variant="ragged", waves=0):
+    """Fill an INT8 cache with the context, append the step's rows (separately or through
+    bass_append_verify_attention), verify.  Returns O, lse, status, the DeviceAttention."""
+    import torch
+    import paper_2404_15778_amd as bass
+    da = hip.DeviceAttention(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, "int8kv", w.scale, poison=True)
+    ctx, nq = hip.i32(w.ctx_len), hip.i32(w.draft_len)
+    da.append(hip.to_device(w.K), hip.to_device(w.V), torch.zeros_like(ctx), ctx)
+    Kn = np.zeros((w.B, w.kmax, w.Hkv, w.D), np.uint16)
+    Vn = np.zeros_like(Kn)
+    for b in range(w.B):
+        L, n = int(w.ctx_len[b]), int(w.draft_len[b])
+        Kn[b, :n], Vn[b, :n] = w.K[b, L:L + n], w.V[b, L:L + n]
+    Q = hip.to_device(w.Q)
+    bass.bass_set_attention_waves(waves)
+    try:
+        if two_step:
+            da.append(hip.to_device(Kn), hip.to_device(Vn), ctx, nq)
+            O, lse = da.verify(Q, ctx, nq, variant=variant, padded_len=int((w.ctx_len + w.draft_len).max()))
+        else:
+            O, lse = da.append_verify(Q, hip.to_device(Kn), hip.to_device(Vn), ctx, nq)
+        torch.cuda.synchronize()
+    finally:
+        bass.bass_set_attention_waves(0)
+    return hip.to_host(O), hip.to_host(lse), int(da.status.item()), da
+
+
+def check(hip, w, **kw):
+    import torch
+    (Kq, Ks, Vq, Vs), Or, lser = reference(w)
+    O, lse, status, da = run(hip, w, **kw)
+    assert status == 0 and np.isfinite(O).all() and np.isfinite(lse).all()
+    assert np.abs(O - Or).max() <= TOL
+    assert np.abs(lse - lser).max() <= TOL
+    total = w.ctx_len + w.draft_len
+    n = int(total.max())
+    got = [hip.to_host(t) for t in da.gather_int8(hip.i32(np.zeros(w.B)), hip.i32(total), n)]
+    torch.cuda.synchronize()
+    for b in range(w.B):
+        t = int(total[b])
+        np.testing.assert_array_equal(got[0][b, :t], Kq[b, :t])       # codes bit for bit
+        np.testing.assert_array_equal(got[1][b, :t], Vq[b, :t])
+        np.testing.assert_array_equal(got[2][b, :t], Ks[b, :t])       # scales bit for bit
+        np.testing.assert_array_equal(got[3][b, :t], Vs[b, :t])
+
+
+@pytest.mark.parametrize("D", [128, 64])
+@pytest.mark.parametrize("waves", [0, 64, 1024])
+def test_int8_cache_mha(hip, D, waves):
+    w = wl.make_attention("i8", 5, 8, 8, D, "bf16", [30, 63, 0, 500, 129], [6, 3, 2, 5, 0], 17, kmax=6, Lcap=520)
+    check(hip, w, waves=waves)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,kmax", [(128, 16, 4, 4), (128, 16, 2, 6), (64, 16, 2, 8), (128, 8, 1, 8)])
+def test_int8_cache_gqa_tiles(hip, D, Hq, Hkv, kmax):
+    # 16, 48, 64 and 64 query rows per kv head: one to four tiles
+    nq = [kmax, max(1, kmax - 2), 1]
+    w = wl.make_attention("i8g", 3, Hq, Hkv, D, "bf16", [100, 37, 260], nq, 23, kmax=kmax, Lcap=300)
+    check(hip, w)
+
+
+@pytest.mark.parametrize("ctx", [31, 32, 33, 64])
+def test_int8_block_boundaries_and_the_one_call_entry_point(hip, ctx):
+    w = wl.make_attention("i8e", 2, 4, 4, 128, "bf16", [ctx, ctx - 1], [1, 2], ctx, kmax=2, Lcap=96)
+    check(hip, w, two_step=False)      # bass_append_verify_attention: quantizing append + attention
+
+
+@pytest.mark.parametrize("variant", ["pad", "split"])
+def test_int8_pad_and_split_variants(hip, variant):
+    w = wl.make_attention("i8v", 4, 8, 4, 128, "bf16", [30, 200, 0, 77], [3, 2, 1, 4], 31, kmax=4, Lcap=220)
+    check(hip, w, variant=variant)
+
+
+def test_int8_rows_of_zeros_and_extreme_rows(hip):
+    w = wl.make_attention("i8z", 2, 4, 4, 128, "bf16", [40, 20], [2, 1], 41, kmax=2, Lcap=64)
+    w.K[0, 3] = 0                                                  # a key row of zeros: scale 0, codes 0
+    w.V[1, 5] = 0
+    w.V[0, 7] = wl.to_bf16_bits(np.full((4, 128), 3.0, np.float32))   # constant row: every code 127
+    big = np.zeros((4, 128), np.float32)
+    big[:, 0] = 1e4                                                # one huge element flattens the rest to 0
+    w.K[1, 2] = wl.to_bf16_bits(big)
+    check(hip, w)
+
+
+def test_int8_cache_is_about_half_the_bytes(hip):
+    import paper_2404_15778_amd as bass
+    a = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "bf16", 1.0))
+    b = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "int8kv", 1.0))
+    assert abs(b / a - (128 + 4) / 256) < 1e-9   # D + 4 bytes per token and head instead of 2 D
