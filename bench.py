@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--separate-append", action="store_true", help="bass_kv_append + bass_verify_attention as two launches")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic for counter scaling)")
+    ap.add_argument("--kv-int8", action="store_true",
+                    help="INT8 KV caches with per-token, per-head scales (not the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -84,7 +86,7 @@ def main():
     NL = args.layers
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234 + args.seed)
-    desc = bass.make_desc(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, "bf16", w.scale)
+    desc = bass.make_desc(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, "int8kv" if args.kv_int8 else "bf16", w.scale)
     ctx, nq = harness.i32(w.ctx_len, dev), harness.i32(w.draft_len, dev)
     zero = torch.zeros_like(ctx)
     Lmax = int(w.ctx_len.max())
@@ -209,6 +211,8 @@ def main():
     del lt, ld, pw, qw
 
     kv_bytes = w.kv_bytes  # per layer
+    if args.kv_int8:  # D codes + one fp32 scale per token and head instead of 2 D bytes
+        kv_bytes = kv_bytes * (w.D + 4) // (2 * w.D)
     step_bytes = kv_bytes * NL
     value = step_bytes / (wall / args.steps) / 1e9
     n_acc_host = harness.to_host(n_accept)
@@ -223,16 +227,17 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16 (INT8 KV cache)" if args.kv_int8 else "bf16",
         "data": "synthetic",
         "config": {
-            "workload": "cfg5 full verification step = cfg2 ragged MHA verify attention (B=8, Hq=Hkv=32, D=128, bf16, "
+            "workload": "cfg5 full verification step = cfg2 ragged MHA verify attention (B=8, Hq=Hkv=32, D=128, "
+                        + ("bf16 Q, INT8 KV cache, " if args.kv_int8 else "bf16, ") +
                         f"ctx U[512,2048], drafts U[1,6]) x {NL} layers + spec_accept (V=50000, k=5)",
             "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "layers": NL, "seed": args.seed,
             "ctx_len": w.ctx_len.tolist(), "draft_len": w.draft_len.tolist(),
             "kv_bytes_per_layer": kv_bytes, "attention_waves": bass.bass_set_attention_waves(args.waves),
             "launch": "eager" if args.no_graph else "hip_graph_replay",
-            "append": "separate launch" if args.separate_append else "fused into the attention launch",
+            "append": "separate launch" if (args.separate_append or args.kv_int8) else "fused into the attention launch",
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "verified_tokens_per_s": round(w.verified_tokens / (wall / args.steps), 1),
@@ -241,13 +246,14 @@ def main():
         "spec_accept_us": round(accept_us, 2),
         "logit_warp_us": round(warp_us, 2),
         "roofline": {
-            "kernel": "verify_attn_bf16<128,1> (append + streaming + split-context reduction, one launch)",
+            "kernel": ("kv_rows_i8_append + verify_attn_bf16<128,1,int8> (two launches)" if args.kv_int8 else
+                       "verify_attn_bf16<128,1> (append + streaming + split-context reduction, one launch)"),
             "bound": "hbm",
             "achieved": round(kv_bytes / (attn_us * 1e-6) / 1e9, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(kv_bytes / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-            "traffic": measured_traffic(),
+            "traffic": None if args.kv_int8 else measured_traffic(),
         },
     }
 

@@ -51,8 +51,10 @@ static long long* g_trace = nullptr;
 
 // many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
 // launch merges the partials there, and a slightly wider spread measured best (896)
-static int attention_waves(bool many_rows = false) {
-  int w = g_attention_waves > 0 ? g_attention_waves : (many_rows ? 896 : kDefaultWaves);
+// int8: INT8 caches; the kernel is bound by the conversion instructions there, not by memory, and
+// uses every SIMD (1024)
+static int attention_waves(bool many_rows = false, bool int8 = false) {
+  int w = g_attention_waves > 0 ? g_attention_waves : (int8 ? 1024 : many_rows ? 896 : kDefaultWaves);
   if (w < 64) w = 64;
   if (w > kMaxWaves) w = kMaxWaves;
   return w - w % g_wpw;
@@ -1251,7 +1253,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   read_pad_override();
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
-  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16);
+  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
   p.pad = K_new ? g_append_pad : g_plain_pad;
   p.span = span;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
