@@ -42,6 +42,9 @@ static int g_attention_waves = 0;  // 0 = default
 static int g_append_pad = 3;      // virtual blocks per unit when the append is fused (measured best: 3)
 static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
 static int g_wpw = 4;             // wavefronts per workgroup
+// Diagnostic build only (-DBASS_EXP_TRACE): every wavefront records wall-clock stamps of its phases
+// (schedule known, streaming done, stores acknowledged, arrival counted, delivered) into a caller's
+// buffer of 16 int64 per wavefront; the product build compiles none of it.
 #ifdef BASS_EXP_TRACE
 static long long* g_trace = nullptr;
 #define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
@@ -933,12 +936,6 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       const ptrdiff_t own = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec + lane;  // this lane's chunks of block s
       uint4* kdst = (uint4*)const_cast<void*>(p.Kc) + own;
       uint4* vdst = (uint4*)const_cast<void*>(p.Vc) + own;
-#ifdef BASS_EXP_NOCOMPUTE
-      unsigned xx = 0;
-      for (int i = 0; i < 2 * (D / 32); ++i) xx ^= r.k[i].x ^ r.k[i].y ^ r.k[i].z ^ r.k[i].w;
-      for (int i = 0; i < D / 16; ++i) xx ^= r.v[i].x ^ r.v[i].y ^ r.v[i].z ^ r.v[i].w;
-      st.l[0] += __uint_as_float(xx & 0x3f800000u);
-#else
       if constexpr (kI8) {
         KvRegs<D> t;
         TokenScales sc;
@@ -948,7 +945,6 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       } else {
         block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
       }
-#endif
     };
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
@@ -1003,9 +999,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 #ifdef BASS_EXP_TRACE
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
 #endif
-#ifndef BASS_EXP_NOCOMBINE
     if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane);
-#endif
     BASS_TRACE(6);
     x += spanA + spanB;
   }
