@@ -79,6 +79,61 @@ __global__ __launch_bounds__(256) void kv_rows_bf16(KvParams p) {
   }
 }
 
+// Appends of many rows (a prompt, a moved sequence): one workgroup per (sequence, kv head, 32-token
+// cache block).  K rows go out as the 16-byte chunks they already are; the V tile is turned in LDS so
+// that the cache receives whole 16-byte chunks (eight tokens of one head element) instead of 2-byte
+// scatters.  A block that the rows cover only partly keeps its other tokens (read-modify-write; no
+// other workgroup touches the block).
+template <int D>
+__global__ __launch_bounds__(256) void kv_blocks_bf16(KvParams p, int blocks_per_seq) {
+  __shared__ __align__(16) uint16_t vt[kBlockTokens][D + 8];
+  const int tid = threadIdx.x;
+  const int j = blockIdx.x % blocks_per_seq;
+  const int unit = blockIdx.x / blocks_per_seq;
+  const int kvh = unit % p.Hkv, b = unit / p.Hkv;
+  int n = p.cnt[b];
+  bool bad = false;
+  if (n < 0) { n = 0; bad = true; }
+  if (n > p.kmax) { n = p.kmax; bad = true; }
+  const long off = p.off[b];
+  const long lo = max(off, 0l), hi = min(off + n, (long)p.Lcap);  // tokens that exist in the cache
+  if (n > 0 && (off < 0 || off + n > p.Lcap)) bad = true;
+  if (bad && j == 0 && kvh == 0 && tid == 0 && p.status) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
+  if (hi <= lo) return;
+  const int blk = (int)(lo / kBlockTokens) + j;
+  const long t0 = max(lo, (long)blk * kBlockTokens), t1 = min(hi, (long)(blk + 1) * kBlockTokens);
+  if (t1 <= t0) return;  // uniform for the workgroup
+  const size_t base = (((size_t)b * p.Hkv + kvh) * p.nblk + blk) * ((size_t)kBlockTokens * D);
+  uint16_t* kc = (uint16_t*)p.Kc + base;
+  uint16_t* vc = (uint16_t*)p.Vc + base;
+  constexpr int CPR = D / 8;  // 16-byte chunks per row
+  for (int c = tid; c < kBlockTokens * CPR; c += 256) {
+    const int w = c / CPR, ck = c % CPR;
+    const long tok = (long)blk * kBlockTokens + w;
+    if (tok >= t0 && tok < t1) {
+      const size_t src = ((((size_t)b * p.kmax + (size_t)(tok - off)) * p.Hkv + kvh) * D) + ck * 8;
+      *(uint4*)(kc + k_elem_offset(D, w, ck * 8)) = *(const uint4*)((const uint16_t*)p.Kr + src);
+      *(uint4*)&vt[w][ck * 8] = *(const uint4*)((const uint16_t*)p.Vr + src);
+    }
+  }
+  __syncthreads();
+  const bool whole = t0 == (long)blk * kBlockTokens && t1 == (long)(blk + 1) * kBlockTokens;
+  for (int c = tid; c < (D / 16) * 64; c += 256) {
+    const int mt = c / 64, l = c % 64, grp = l >> 4, dr = l & 15;
+    uint4* dst = (uint4*)(vc + (size_t)c * 8);
+    uint4 cur = make_uint4(0, 0, 0, 0);
+    if (!whole) cur = *dst;
+    uint16_t* e = (uint16_t*)&cur;
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      const int w = jj < 4 ? 4 * grp + jj : 16 + 4 * grp + (jj - 4);
+      const long tok = (long)blk * kBlockTokens + w;
+      if (whole || (tok >= t0 && tok < t1)) e[jj] = vt[w][16 * mt + dr];
+    }
+    *dst = cur;
+  }
+}
+
 template <bool kGather>
 __global__ __launch_bounds__(256) void kv_rows_fp32(KvParams p) {
   const int chunks = p.D / 4;
@@ -212,9 +267,16 @@ static int launch_rows(const bass_attn_desc* d, void* Kc, void* Vc, void* Kr, vo
   if (d->dtype == BASS_DTYPE_INT8KV) {
     if (kGather) hipLaunchKernelGGL(kv_rows_i8_gather, grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(kv_rows_i8_append, grid, dim3(256), 0, s, p);
-  } else if (d->dtype == BASS_DTYPE_BF16)
-    hipLaunchKernelGGL(kv_rows_bf16<kGather>, grid, dim3(256), 0, s, p);
-  else
+  } else if (d->dtype == BASS_DTYPE_BF16) {
+    const int64_t per_seq = (d->kmax + kBlockTokens - 1) / kBlockTokens + 1;  // blocks the rows of a sequence can touch
+    const int64_t wgs = (int64_t)d->B * d->Hkv * per_seq;
+    if (!kGather && d->kmax >= kBlockTokens && wgs <= 0x7fffffff) {
+      if (d->D == 128) hipLaunchKernelGGL(kv_blocks_bf16<128>, dim3((unsigned)wgs), dim3(256), 0, s, p, (int)per_seq);
+      else hipLaunchKernelGGL(kv_blocks_bf16<64>, dim3((unsigned)wgs), dim3(256), 0, s, p, (int)per_seq);
+    } else {
+      hipLaunchKernelGGL(kv_rows_bf16<kGather>, grid, dim3(256), 0, s, p);
+    }
+  } else
     hipLaunchKernelGGL(kv_rows_fp32<kGather>, grid, dim3(256), 0, s, p);
   return launch_status();
 }

@@ -142,3 +142,43 @@ def test_gqa_equals_mha_with_repeated_kv_heads_on_gpu(hip):
     Om, _, _, _ = hip.run_attention_workload(m)
     # same numbers, different work decomposition: equal up to the split-context rounding
     assert np.abs(O - Om).max() <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("bf16", 64), ("fp32", 64)])
+def test_long_appends_at_unaligned_offsets_keep_their_neighbours(hip, dtype, D):
+    # many rows at once (a prompt, a moved sequence) take the block-wise path of the bf16 cache: blocks that
+    # the rows cover only partly keep their other tokens; rows beyond the cache are dropped and reported
+    import torch
+    import paper_2404_15778_amd as bass
+    B, H, Lcap = 3, 2, 200
+    first = [40, 0, 33]          # tokens already there
+    more = [70, 100, 64]         # rows appended behind them in one call
+    w = wl.make_attention("long_append", B, H, H, D, dtype, [a + b for a, b in zip(first, more)], [1, 1, 1], 3,
+                          kmax=1, Lcap=Lcap)
+    da = hip.DeviceAttention(B, 1, H, H, D, Lcap, dtype, w.scale, poison=True)
+    K, V = w.K, w.V
+    n1, n2 = max(first), max(more)
+    A = np.zeros((B, n1, H, D), K.dtype)
+    Av = np.zeros_like(A)
+    Bk = np.zeros((B, n2, H, D), K.dtype)
+    Bv = np.zeros_like(Bk)
+    for b in range(B):
+        A[b, :first[b]], Av[b, :first[b]] = K[b, :first[b]], V[b, :first[b]]
+        Bk[b, :more[b]], Bv[b, :more[b]] = K[b, first[b]:first[b] + more[b]], V[b, first[b]:first[b] + more[b]]
+    da.append(hip.to_device(A), hip.to_device(Av), hip.i32([0] * B), hip.i32(first))
+    da.append(hip.to_device(Bk), hip.to_device(Bv), hip.i32(first), hip.i32(more))
+    total = np.array(first) + np.array(more)
+    Kg, Vg = da.gather(hip.i32([0] * B), hip.i32(total), int(total.max()))
+    torch.cuda.synchronize()
+    Kg, Vg = hip.to_host(Kg), hip.to_host(Vg)
+    for b in range(B):
+        np.testing.assert_array_equal(Kg[b, :total[b]], K[b, :total[b]])
+        np.testing.assert_array_equal(Vg[b, :total[b]], V[b, :total[b]])
+    assert int(da.status.item()) == 0
+    # rows that would run past the capacity are dropped and reported, the ones inside are written
+    da.append(hip.to_device(Bk), hip.to_device(Bv), hip.i32([Lcap - 10, 0, 0]), hip.i32([64, 0, 0]))
+    torch.cuda.synchronize()
+    assert int(da.status.item()) & bass.STATUS_LEN_CLAMPED
+    Kg, _ = da.gather(hip.i32([Lcap - 10, 0, 0]), hip.i32([10, 0, 0]), 10)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(hip.to_host(Kg)[0, :10], Bk[0, :10])
