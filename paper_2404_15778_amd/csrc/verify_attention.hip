@@ -1,4 +1,6 @@
-// Ragged verify attention of libbass: bass_verify_attention.
+// Ragged verify attention of libbass: bass_verify_attention, bass_append_verify_attention (the
+// step's K/V rows appended inside the same launch), bass_verify_attention_pad / _split (the paper's
+// BASS-PAD and BASS-SPLIT as launch variants), for bf16, INT8 and fp32 caches.
 //
 // BASS paper, Section 3.2 (attention flow): scores of the current tokens' queries against
 // the keys of all tokens processed so far, P = softmax(Q^T K / c), then P times V, with
@@ -17,7 +19,9 @@
 // sum per query row) and, for every unit it touches, writes one partial (max, sum,
 // unnormalised output).  The wavefront that delivers the LAST partial of a unit (found with
 // one atomic counter per unit) merges the unit's partials -- the split-context reduction --
-// and writes O and the log-sum-exp, so the whole call is a single launch.
+// and writes O and the log-sum-exp, so the whole call is a single launch.  (With more than one
+// 16-row query tile per kv head -- grouped-query attention -- the merge is a second, chip-wide
+// launch: reduce_partials.)
 //
 // Matrix-core mapping (v_mfma_f32_16x16x32_bf16, wave64).  Tokens sit on the M side:
 //   S^T[16 tokens x 16 query rows] = K[16 x D] * Q^T[D x 16]          (D/32 MFMAs per tile)
