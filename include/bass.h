@@ -132,7 +132,9 @@ int bass_kv_gather(const bass_attn_desc* desc, const void* Kcache, const void* V
  * Lengths outside the cache are clamped (BASS_STATUS_LEN_CLAMPED).
  * bf16: kmax * (Hq/Hkv) <= 64.  `workspace` must hold at least
  * bass_verify_attention_workspace_bytes(desc) bytes, be 16-byte aligned and have been zeroed
- * once (see above).  One launch: the split-context reduction runs inside the same kernel.
+ * once (see above).  One launch when a kv head has at most 16 query rows (kmax * Hq/Hkv <= 16): the
+ * split-context reduction runs inside the same kernel; with more rows a second, chip-wide launch
+ * merges the partial results.
  */
 int bass_verify_attention(const bass_attn_desc* desc, const void* Q, const void* Kcache,
                           const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
@@ -166,10 +168,12 @@ int bass_verify_attention_split(const bass_attn_desc* desc, const void* Q, const
  * bass_kv_append and bass_verify_attention in ONE launch: appends rows i < draft_len[b] of K_new,
  * V_new [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
  * bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, ...) would, and computes
- * bass_verify_attention over the updated caches.  The cache contents are identical to those after
- * the two separate calls; O and lse agree with them up to rounding (the fused launch cuts the
+ * bass_verify_attention over the updated caches.  The valid tokens of the caches are identical to those
+ * after the two separate calls (stale rows beyond a sequence's new length may differ); O and lse agree with them up to rounding (the fused launch cuts the
  * context at other points).  Rows of sequences whose lengths had to be clamped are appended at the
- * clamped positions.  Arguments as in those calls.
+ * clamped positions.  Arguments as in those calls.  bf16 caches with kmax * D <= 2048 and fp32 caches
+ * append inside the attention launch; longer drafts and INT8 caches (whose rows are quantized by the
+ * append kernel) run the append as a launch of its own inside this call.
  */
 int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, const void* K_new,
                                  const void* V_new, void* Kcache, void* Vcache,
