@@ -165,15 +165,16 @@ int bass_verify_attention_split(const bass_attn_desc* desc, const void* Q, const
                                 size_t workspace_bytes, int32_t* dev_status, void* stream);
 
 /*
- * bass_kv_append and bass_verify_attention in ONE launch: appends rows i < draft_len[b] of K_new,
+ * bass_kv_append and bass_verify_attention in ONE call: appends rows i < draft_len[b] of K_new,
  * V_new [B, kmax, Hkv, D] at cache tokens ctx_len[b] + i, exactly as
  * bass_kv_append(desc, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, ...) would, and computes
- * bass_verify_attention over the updated caches.  The valid tokens of the caches are identical to those
- * after the two separate calls (stale rows beyond a sequence's new length may differ); O and lse agree with them up to rounding (the fused launch cuts the
- * context at other points).  Rows of sequences whose lengths had to be clamped are appended at the
- * clamped positions.  Arguments as in those calls.  bf16 caches with kmax * D <= 2048 and fp32 caches
- * append inside the attention launch; longer drafts and INT8 caches (whose rows are quantized by the
- * append kernel) run the append as a launch of its own inside this call.
+ * bass_verify_attention over the updated caches.  The valid tokens of the caches are identical to
+ * those after the two separate calls (stale rows beyond a sequence's new length may differ); O and
+ * lse agree with them up to rounding (the fused launch cuts the context at other points).  Rows of
+ * sequences whose lengths had to be clamped are appended at the clamped positions.  Arguments as
+ * in those calls.  bf16 caches with kmax * D <= 2048 and fp32 caches append inside the attention
+ * launch; longer drafts and INT8 caches (whose rows are quantized by the append kernel) run the
+ * append as a launch of its own inside this call.
  */
 int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, const void* K_new,
                                  const void* V_new, void* Kcache, void* Vcache,
