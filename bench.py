@@ -237,7 +237,7 @@ def main():
             "ctx_len": w.ctx_len.tolist(), "draft_len": w.draft_len.tolist(),
             "kv_bytes_per_layer": kv_bytes, "attention_waves": bass.bass_set_attention_waves(args.waves),
             "launch": "eager" if args.no_graph else "hip_graph_replay",
-            "append": "separate launch" if (args.separate_append or args.kv_int8) else "fused into the attention launch",
+            "append": "separate launch" if args.separate_append else "fused into the attention launch",
         },
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "verified_tokens_per_s": round(w.verified_tokens / (wall / args.steps), 1),
@@ -246,7 +246,8 @@ def main():
         "spec_accept_us": round(accept_us, 2),
         "logit_warp_us": round(warp_us, 2),
         "roofline": {
-            "kernel": ("kv_rows_i8_append + verify_attn_bf16<128,1,int8> (two launches)" if args.kv_int8 else
+            "kernel": ("verify_attn_bf16<128,1,int8> (quantizing append + streaming + split-context reduction, one launch)"
+                       if args.kv_int8 else
                        "verify_attn_bf16<128,1> (append + streaming + split-context reduction, one launch)"),
             "bound": "hbm",
             "achieved": round(kv_bytes / (attn_us * 1e-6) / 1e9, 1),

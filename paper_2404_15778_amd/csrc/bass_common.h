@@ -67,6 +67,32 @@ __host__ __device__ inline size_t i8_v_offset(int /*D*/, int tok_in_blk, int d) 
   return (size_t)(((f >> 1) * 64 + lane) * 16 + (f & 1) * 8 + j);
 }
 
+// Quantizer of the INT8 caches (see bass.h, BASS_DTYPE_INT8KV): every step is one fp32 operation.
+#ifdef __HIPCC__
+__device__ inline float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// codes of 8 bf16 values (in a uint4) for the row scale 127 / amax; returns them packed in 8 bytes
+__device__ inline uint2 quantize8(const uint4& v, float inv) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  uint32_t out[2] = {0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float x = bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
+    const int code = (int)__builtin_rintf(x * inv);  // one fp32 product, round half to even
+    out[e >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (e & 3));
+  }
+  return make_uint2(out[0], out[1]);
+}
+
+__device__ inline float amax8(const uint4& v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float m = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu)));
+  return m;
+}
+#endif
+
 // Per-sequence lengths with the clamping the header promises.  L = cached tokens before the
 // step, nq = query tokens; on return 0 <= nq <= kmax, 0 <= L, L + nq <= Lcap.
 __device__ inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {

@@ -161,29 +161,6 @@ __global__ __launch_bounds__(256) void kv_rows_fp32(KvParams p) {
 // threads of a row are consecutive lanes of one wavefront and agree on the row's largest
 // magnitude through shuffles, so no thread may leave before them.
 // ---------------------------------------------------------------------------------------
-__device__ inline float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
-
-// codes of 8 bf16 values (in a uint4) for the row scale 127 / amax; returns them packed in 8 bytes
-__device__ inline uint2 quantize8(const uint4& v, float inv) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-  uint32_t out[2] = {0u, 0u};
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float x = bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu);
-    const int code = (int)__builtin_rintf(x * inv);  // one fp32 product, round half to even
-    out[e >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (e & 3));
-  }
-  return make_uint2(out[0], out[1]);
-}
-
-__device__ inline float amax8(const uint4& v) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-  float m = 0.f;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xFFFFu)));
-  return m;
-}
-
 __global__ __launch_bounds__(256) void kv_rows_i8_append(KvParams p) {
   const int chunks = p.D / 8;  // 8 or 16: a row's threads share an aligned group of lanes
   const long total = (long)p.B * p.kmax * p.Hkv * chunks;

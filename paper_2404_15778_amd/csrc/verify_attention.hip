@@ -553,7 +553,8 @@ __device__ inline void dequant_block(const KvRegsI8<D>& q, KvRegs<D>& r, TokenSc
 extern __shared__ __align__(16) unsigned char new_rows_lds[];
 
 struct NewRows {
-  unsigned k_off, v_off;  // byte offsets of the unit's K and V rows ([row][D] bf16) in new_rows_lds
+  unsigned k_off, v_off;    // byte offsets of the unit's K and V rows in new_rows_lds: [row][D] bf16, or INT8 codes
+  unsigned ks_off, vs_off;  // INT8 caches: the rows' fp32 scales
   int L, nq;
 };
 
@@ -601,6 +602,90 @@ __device__ inline void stage_commit(const Unit& u, int c0, int lane, const Stage
       *(u32x4*)&new_rows_lds[nr.k_off + 16 * c] = sr.k[i];
       *(u32x4*)&new_rows_lds[nr.v_off + 16 * c] = sr.v[i];
     }
+  }
+}
+
+// INT8 caches: the staged rows are quantized on the way into LDS (codes [row][D] bytes, one fp32 scale
+// per row), exactly as the append kernel does; a row's D/8 chunks sit in consecutive lanes.
+template <int D>
+__device__ inline void stage_commit_i8(const Unit& u, int c0, int lane, const StageRegs& sr, const NewRows nr) {
+  constexpr int CPR = D / 8;
+  const int nchunks = u.nq * CPR;
+#pragma unroll
+  for (int i = 0; i < kStageLoads; ++i) {
+    if (c0 + i * 64 < nchunks) {  // wave-uniform
+      const int c = c0 + i * 64 + lane;
+      const uint4 kv = __builtin_bit_cast(uint4, sr.k[i]), vv = __builtin_bit_cast(uint4, sr.v[i]);
+      float ka = amax8(kv), va = amax8(vv);
+#pragma unroll
+      for (int o = CPR >> 1; o >= 1; o >>= 1) {
+        ka = fmaxf(ka, __shfl_xor(ka, o));
+        va = fmaxf(va, __shfl_xor(va, o));
+      }
+      if (c < nchunks) {
+        const float kinv = ka > 0.f ? 127.0f / ka : 0.f;
+        const float vinv = va > 0.f ? 127.0f / va : 0.f;
+        *(uint2*)&new_rows_lds[nr.k_off + 8 * c] = quantize8(kv, kinv);
+        *(uint2*)&new_rows_lds[nr.v_off + 8 * c] = quantize8(vv, vinv);
+        if (c % CPR == 0) {
+          *(float*)&new_rows_lds[nr.ks_off + 4 * (c / CPR)] = ka / 127.0f;
+          *(float*)&new_rows_lds[nr.vs_off + 4 * (c / CPR)] = va / 127.0f;
+        }
+      }
+    }
+  }
+}
+
+// INT8 caches, fused append: put the new tokens' codes and scales into the fetched block (before it is
+// widened) and write them into the cache block at kblk / vblk (first byte of the block).
+template <int D>
+__device__ inline void patch_block_i8(KvRegsI8<D>& q, int tok0, const NewRows nr, int lane, uint8_t* kblk, uint8_t* vblk) {
+  constexpr int KS = D / 32, MT = D / 16;
+  const int dr = lane & 15, grp = lane >> 4;
+  // K: fragment f = tl * KS + t of a lane is token 16 tl + lane % 16, head elements 32 t + 8 grp .. + 7
+#pragma unroll
+  for (int tl = 0; tl < 2; ++tl) {
+    const int i = tok0 + 16 * tl + dr - nr.L;
+    if (i >= 0 && i < nr.nq) {
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        const int f = tl * KS + t;
+        const uint2 c = *(const uint2*)&new_rows_lds[nr.k_off + i * D + 32 * t + 8 * grp];
+        q.k[f >> 1][2 * (f & 1)] = c.x;
+        q.k[f >> 1][2 * (f & 1) + 1] = c.y;
+        *(uint2*)(kblk + ((f >> 1) * 64 + lane) * 16 + (f & 1) * 8) = c;
+      }
+    }
+  }
+  // V codes and both scales: slot j of a lane is token 4 grp + j (j < 4) or 16 + 4 grp + j - 4
+  bool v_new = false;
+  float* kscale = (float*)(kblk + kBlockTokens * D);
+  float* vscale = (float*)(vblk + kBlockTokens * D);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int w = j < 4 ? 4 * grp + j : 16 + 4 * grp + (j - 4);
+    const int i = tok0 + w - nr.L;
+    if (i >= 0 && i < nr.nq) {
+      v_new = true;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const uint32_t code = new_rows_lds[nr.v_off + i * D + 16 * mt + dr];
+        const uint32_t word = q.v[mt >> 1][2 * (mt & 1) + (j >> 2)];
+        q.v[mt >> 1][2 * (mt & 1) + (j >> 2)] = (word & ~(0xFFu << (8 * (j & 3)))) | (code << (8 * (j & 3)));
+      }
+      const float ks = *(const float*)&new_rows_lds[nr.ks_off + 4 * i];
+      const float vs = *(const float*)&new_rows_lds[nr.vs_off + 4 * i];
+      q.ks[j >> 2][j & 3] = ks;
+      q.vs[j >> 2][j & 3] = vs;
+      if (dr == 0) {  // one lane per token group writes the scales
+        kscale[w] = ks;
+        vscale[w] = vs;
+      }
+    }
+  }
+  if (v_new) {
+#pragma unroll
+    for (int m = 0; m < D / 32; ++m) *(u32x4*)(vblk + (m * 64 + lane) * 16) = q.v[m];
   }
 }
 
@@ -875,10 +960,14 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 
     // fused append: the units whose new tokens lie in our blocks get their rows staged in LDS
     const bool fused = p.Knew != nullptr;
-    const unsigned lds_rows = (unsigned)p.kmax * D * 2;  // bytes of one unit's K (or V) rows
-    const unsigned lds_base = (threadIdx.x >> 6) * 4 * lds_rows;
-    const NewRows newA{lds_base, lds_base + lds_rows, uA.L, uA.nq};
-    const NewRows newB{lds_base + 2 * lds_rows, lds_base + 3 * lds_rows, uB.L, uB.nq};
+    // one unit's slice: K rows, V rows (bf16, or INT8 codes), then for INT8 the rows' K and V scales
+    const unsigned lds_rows = (unsigned)p.kmax * D * (kI8 ? 1 : 2);
+    const unsigned lds_unit = 2 * lds_rows + (kI8 ? 8 * (unsigned)p.kmax : 0);
+    const unsigned lds_base = (threadIdx.x >> 6) * 2 * lds_unit;
+    const NewRows newA{lds_base, lds_base + lds_rows, lds_base + 2 * lds_rows, lds_base + 2 * lds_rows + 4 * (unsigned)p.kmax,
+                       uA.L, uA.nq};
+    const NewRows newB{newA.k_off + lds_unit, newA.v_off + lds_unit, newA.ks_off + lds_unit, newA.vs_off + lds_unit,
+                       uB.L, uB.nq};
     NewRows cur_new = newA;
     const bool stageA = fused && uA.nq > 0 && (x - uA.begin + nA) * kBlockTokens > uA.L;
     const bool stageB = fused && hasB && uB.nq > 0 && nB * kBlockTokens > uB.L;
@@ -886,21 +975,25 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     // second unit then lies wholly inside the share) and stages the second unit's rows afterwards
     const bool stage1 = stageA || stageB;
     const Unit& u1 = stageA ? uA : uB;
-    const NewRows& new1 = stageA ? newA : newB;
+    const NewRows new1 = stageA ? newA : newB;  // a copy: a reference would put both structs in memory
     StageRegs sr;
     if (stage1) stage_issue<D>(p, u1, 0, lane, sr);
+    auto commit = [&](const Unit& u, int c0, const StageRegs& regs, const NewRows nr) {
+      if constexpr (kI8) stage_commit_i8<D>(u, c0, lane, regs, nr);
+      else stage_commit<D>(u, c0, lane, regs, nr);
+    };
     // what is left after the overlapped pass (drafts of more than 8 rows, a second unit): rare
     auto stage_rest = [&]() {
       for (int c0 = kStagePass; c0 < u1.nq * (D / 8); c0 += kStagePass) {
         StageRegs sr2;
         stage_issue<D>(p, u1, c0, lane, sr2);
-        stage_commit<D>(u1, c0, lane, sr2, new1);
+        commit(u1, c0, sr2, new1);
       }
       if (stageA && stageB)
         for (int c0 = 0; c0 < uB.nq * (D / 8); c0 += kStagePass) {
           StageRegs sr2;
           stage_issue<D>(p, uB, c0, lane, sr2);
-          stage_commit<D>(uB, c0, lane, sr2, newB);
+          commit(uB, c0, sr2, newB);
         }
     };
 
@@ -941,11 +1034,16 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       uint4* kdst = (uint4*)const_cast<void*>(p.Kc) + own;
       uint4* vdst = (uint4*)const_cast<void*>(p.Vc) + own;
       if constexpr (kI8) {
+        if (fused && (cur_blk + s) * kBlockTokens + kBlockTokens - 1 >= cur_L) {  // the block holds new tokens
+          const ptrdiff_t blk_vec = (s < nA ? vecA : vecB) + (ptrdiff_t)s * kBlkVec;
+          patch_block_i8<D>(r, (cur_blk + s) * kBlockTokens, cur_new, lane,
+                            (uint8_t*)const_cast<void*>(p.Kc) + blk_vec * 16, (uint8_t*)const_cast<void*>(p.Vc) + blk_vec * 16);
+        }
         KvRegs<D> t;
         TokenScales sc;
         dequant_block<D>(r, t, sc);
         block_dispatch<D, NT, true>(t, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, false,
-                                    cur_new, nullptr, nullptr, &sc);
+                                    cur_new, nullptr, nullptr, &sc);  // the codes are patched already: no fused work inside
       } else {
         block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
       }
@@ -956,7 +1054,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       fetch(r0, 0);
       fetch(r1, 1);
       if (stage1) {
-        stage_commit<D>(u1, 0, lane, sr, new1);  // these loads were issued before the fetches
+        commit(u1, 0, sr, new1);  // these loads were issued before the fetches
         stage_rest();
       }
       for (int s = 0; s < n; s += 3) {
@@ -972,7 +1070,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       Regs r0, r1;
       fetch(r0, 0);
       if (stage1) {
-        stage_commit<D>(u1, 0, lane, sr, new1);
+        commit(u1, 0, sr, new1);
         stage_rest();
       }
       for (int s = 0; s < n; s += 2) {
@@ -1243,7 +1341,6 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   const int rows_max = d->kmax * g;
   const bool mfma = d->dtype != BASS_DTYPE_FP32;  // bf16 or INT8 caches: the matrix-core kernel
   if (mfma && rows_max > 64) return BASS_ERR_UNSUPPORTED;
-  if (d->dtype == BASS_DTYPE_INT8KV && K_new) return BASS_ERR_UNSUPPORTED;  // appended by a launch of its own
   // partials of one unit are addressed with 32-bit byte offsets
   if ((int64_t)rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
   if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
@@ -1275,10 +1372,12 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
   } else {
     const int nt = (rows_max + 15) / 16;
-    // LDS slice per wavefront of a fused append: K and V rows of two units
-    const size_t lds = K_new ? (size_t)p.wpw * 4 * d->kmax * d->D * 2 : 0;
+    // LDS slice per wavefront of a fused append: K and V rows of two units (bf16, or INT8 codes + scales)
+    const size_t unit_lds = d->dtype == BASS_DTYPE_INT8KV ? (size_t)2 * d->kmax * d->D + 8 * d->kmax
+                                                          : (size_t)2 * d->kmax * d->D * 2;
+    const size_t lds = K_new ? (size_t)p.wpw * 2 * unit_lds : 0;
 #define BASS_LAUNCH(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN>), grid, block, lds, s, p)
-#define BASS_LAUNCH_I8(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN, true>), grid, block, 0, s, p)
+#define BASS_LAUNCH_I8(DD, NN) hipLaunchKernelGGL((verify_attn_bf16<DD, NN, true>), grid, block, lds, s, p)
     if (d->dtype == BASS_DTYPE_INT8KV) {
       if (d->D == 128) {
         if (nt == 1) BASS_LAUNCH_I8(128, 1); else if (nt == 2) BASS_LAUNCH_I8(128, 2);
@@ -1354,10 +1453,8 @@ extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void*
                                             const int32_t* draft_len, float* O, float* lse, void* workspace,
                                             size_t workspace_bytes, int32_t* dev_status, void* stream) {
   if (!K_new || !V_new) return BASS_ERR_INVALID_ARG;
-  if (d && (d->dtype == BASS_DTYPE_INT8KV ||
-            (d->dtype == BASS_DTYPE_BF16 && (int64_t)d->kmax * d->D > bass::kMaxStagedElems))) {
-    // INT8 caches (rows are quantized by the append kernel), or more new rows than a wavefront stages
-    // in LDS: append with a launch of its own
+  if (d && d->dtype != BASS_DTYPE_FP32 && (int64_t)d->kmax * d->D > bass::kMaxStagedElems) {
+    // more new rows than a wavefront stages in LDS: append with a launch of its own
     const int rc = bass_kv_append(d, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, dev_status, stream);
     if (rc != BASS_OK) return rc;
     return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,

@@ -78,17 +78,30 @@ def check(hip, w, **kw):
 
 @pytest.mark.parametrize("D", [128, 64])
 @pytest.mark.parametrize("waves", [0, 64, 1024])
-def test_int8_cache_mha(hip, D, waves):
+@pytest.mark.parametrize("two_step", [True, False])
+def test_int8_cache_mha(hip, D, waves, two_step):
+    # two_step False: bass_append_verify_attention quantizes and appends the step's rows inside the launch
     w = wl.make_attention("i8", 5, 8, 8, D, "bf16", [30, 63, 0, 500, 129], [6, 3, 2, 5, 0], 17, kmax=6, Lcap=520)
-    check(hip, w, waves=waves)
+    check(hip, w, waves=waves, two_step=two_step)
 
 
 @pytest.mark.parametrize("D,Hq,Hkv,kmax", [(128, 16, 4, 4), (128, 16, 2, 6), (64, 16, 2, 8), (128, 8, 1, 8)])
-def test_int8_cache_gqa_tiles(hip, D, Hq, Hkv, kmax):
+@pytest.mark.parametrize("two_step", [True, False])
+def test_int8_cache_gqa_tiles(hip, D, Hq, Hkv, kmax, two_step):
     # 16, 48, 64 and 64 query rows per kv head: one to four tiles
     nq = [kmax, max(1, kmax - 2), 1]
     w = wl.make_attention("i8g", 3, Hq, Hkv, D, "bf16", [100, 37, 260], nq, 23, kmax=kmax, Lcap=300)
-    check(hip, w)
+    check(hip, w, two_step=two_step)
+
+
+@pytest.mark.parametrize("D,kmax,Hq,Hkv", [(128, 12, 4, 4), (128, 16, 2, 2), (64, 32, 2, 2), (128, 20, 2, 2), (64, 24, 4, 2)])
+@pytest.mark.parametrize("waves", [0, 64])
+def test_int8_fused_append_with_long_drafts(hip, D, kmax, Hq, Hkv, waves):
+    # more than 8 rows of 128: several quantizing copies inside the launch; beyond kmax * D = 2048 the append
+    # runs as a launch of its own
+    w = wl.make_attention("i8long", 5, Hq, Hkv, D, "bf16", [100, 37, 31, 0, 60], [kmax, kmax - 3, 9, kmax, 1], 21,
+                          kmax=kmax, Lcap=160)
+    check(hip, w, two_step=False, waves=waves)
 
 
 @pytest.mark.parametrize("ctx", [31, 32, 33, 64])
