@@ -18,8 +18,8 @@
 // bit patterns of e_i (positive floats order like their bit patterns): four passes of 8 bits, each
 // a mass histogram per wavefront in LDS (64-bit LDS atomics) followed by a suffix scan over the 256
 // bins.  Tokens that tie with the threshold value are ranked by token id in a pass of their own
-// (rare: it runs only if not all of them are kept).  The row is re-read from L2 in every pass, eight
-// loads per thread in flight at a time.
+// (rare: it runs only if not all of them are kept).  The values e_i are written into the output row in
+// the first pass and re-read from L2 by the later ones (16-byte accesses when rows are aligned).
 #include "bass_common.h"
 
 namespace bass {
@@ -59,8 +59,33 @@ __device__ inline uint64_t wave_incl_scan_u64(uint64_t v, int lane) {
   return v;
 }
 
-constexpr int kWarpUnroll = 8;  // loads a thread keeps in flight
+constexpr int kWarpUnroll = 8;  // groups a thread keeps in flight
 
+// W logits per thread and load: 4 (16-byte loads; V a multiple of 4 and 16-byte aligned rows) or 1
+template <int W>
+struct Group {
+  float v[W];
+};
+
+template <int W>
+__device__ inline Group<W> load_group(const float* row, int g) {
+  Group<W> r;
+  if constexpr (W == 4) {
+    const float4 t = ((const float4*)row)[g];
+    r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+  } else {
+    r.v[0] = row[g];
+  }
+  return r;
+}
+
+template <int W>
+__device__ inline void store_group(float* row, int g, const Group<W>& r) {
+  if constexpr (W == 4) ((float4*)row)[g] = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+  else row[g] = r.v[0];
+}
+
+template <int W>
 __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) {
   __shared__ uint64_t hist[kWarpWaves][256];
   __shared__ uint64_t red64[kWarpWaves];
@@ -72,29 +97,30 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int V = a.V;
+  const int groups = V / W;
   const float* z = a.logits + (size_t)blockIdx.x * V;
   float* out = a.probs + (size_t)blockIdx.x * V;
 
-  // f(i, z_i) for this thread's tokens i = tid, tid + 1024, ...: loads of a batch first, then the work
-  auto for_each_logit = [&](auto f) {
-    for (int base = tid; base < V; base += kWarpUnroll * kWarpThreads) {
-      float zz[kWarpUnroll];
+  // f(g, values) for this thread's groups g = tid, tid + 1024, ... of a row: a batch of loads first, then the work
+  auto for_each_group = [&](const float* row, auto f) {
+    for (int base = tid; base < groups; base += kWarpUnroll * kWarpThreads) {
+      Group<W> gr[kWarpUnroll];
+#pragma unroll
+      for (int k = 0; k < kWarpUnroll; ++k) gr[k] = load_group<W>(row, min(base + k * kWarpThreads, groups - 1));
 #pragma unroll
       for (int k = 0; k < kWarpUnroll; ++k) {
-        const int i = base + k * kWarpThreads;
-        zz[k] = z[min(i, V - 1)];
-      }
-#pragma unroll
-      for (int k = 0; k < kWarpUnroll; ++k) {
-        const int i = base + k * kWarpThreads;
-        if (i < V) f(i, zz[k]);
+        const int g = base + k * kWarpThreads;
+        if (g < groups) f(g, gr[k]);
       }
     }
   };
 
   // largest logit (NaN entries are ignored)
   float m = -INFINITY;
-  for_each_logit([&](int, float zi) { m = fmaxf(m, zi); });
+  for_each_group(z, [&](int, const Group<W>& gr) {
+#pragma unroll
+    for (int e = 0; e < W; ++e) m = fmaxf(m, gr.v[e]);
+  });
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
   if (lane == 0) redf[wave] = m;
@@ -108,8 +134,6 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
     return;
   }
 
-  auto for_each = [&](auto f) { for_each_logit([&](int i, float zi) { f(i, warp_e(zi, zmax, a.c)); }); };
-
   const bool keep_all = a.top_p >= 1.0f;
   uint32_t prefix = 0;   // selected high bits of the threshold key
   uint64_t above = 0;    // mass of keys above the selected prefix
@@ -119,21 +143,21 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
     const int shift = 24 - 8 * pass;
     for (int k = tid; k < kWarpWaves * 256; k += kWarpThreads) (&hist[0][0])[k] = 0;
     __syncthreads();
-    uint64_t mine = 0;
     if (pass == 0) {
-      for_each([&](int, float e) {
-        const uint64_t w = warp_mass(e);
-        mine += w;
-        if (w && !keep_all) atomicAdd((unsigned long long*)&hist[wave][__float_as_uint(e) >> 24], (unsigned long long)w);
+      // e_i from the logits, kept in the output row for the later passes (each thread re-reads what it wrote)
+      uint64_t mine = 0;
+      for_each_group(z, [&](int g, const Group<W>& gr) {
+        Group<W> ev;
+#pragma unroll
+        for (int e = 0; e < W; ++e) {
+          ev.v[e] = warp_e(gr.v[e], zmax, a.c);
+          const uint64_t w = warp_mass(ev.v[e]);
+          mine += w;
+          if (w && !keep_all) atomicAdd((unsigned long long*)&hist[wave][__float_as_uint(ev.v[e]) >> 24], (unsigned long long)w);
+        }
+        store_group<W>(out, g, ev);
       });
-    } else {  // only the tokens of the selected bin take part (e >= 2^-40 there: the mass is not 0)
-      for_each([&](int, float e) {
-        const uint32_t key = __float_as_uint(e);
-        if (e > 0.f && (key >> (shift + 8)) == prefix)
-          atomicAdd((unsigned long long*)&hist[wave][(key >> shift) & 255u], (unsigned long long)warp_mass(e));
-      });
-    }
-    if (pass == 0) {  // total mass and the mass the nucleus has to reach
+      // total mass and the mass the nucleus has to reach
       mine = wave_sum64(mine);
       if (lane == 0) red64[wave] = mine;
       __syncthreads();
@@ -142,6 +166,15 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
       if (t < 1.0) t = 1.0;
       target = keep_all || t >= (double)S ? S : (uint64_t)t;
       if (keep_all) break;
+    } else {  // only the tokens of the selected bin take part (e >= 2^-40 there: the mass is not 0)
+      for_each_group(out, [&](int, const Group<W>& gr) {
+#pragma unroll
+        for (int e = 0; e < W; ++e) {
+          const uint32_t key = __float_as_uint(gr.v[e]);
+          if (gr.v[e] > 0.f && (key >> (shift + 8)) == prefix)
+            atomicAdd((unsigned long long*)&hist[wave][(key >> shift) & 255u], (unsigned long long)warp_mass(gr.v[e]));
+        }
+      });
     }
     if (tid == 0) sh_cross = 256;
     __syncthreads();
@@ -183,9 +216,15 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
   const float inv = (float)((double)kMassScale / (double)K);
   const float e_thr = __uint_as_float(prefix);  // e_i >= 0: floats order like their bit patterns; NaN compares false
 
-  for_each([&](int i, float e) {
-    const bool kept = keep_all ? e > 0.f : (e > e_thr || (e == e_thr && ties_all_kept));
-    out[i] = kept ? e * inv : 0.f;
+  for_each_group(out, [&](int g, const Group<W>& gr) {
+    Group<W> pv;
+#pragma unroll
+    for (int e = 0; e < W; ++e) {
+      const float ei = gr.v[e];
+      const bool kept = keep_all ? ei > 0.f : (ei > e_thr || (ei == e_thr && ties_all_kept));
+      pv.v[e] = kept ? ei * inv : 0.f;
+    }
+    store_group<W>(out, g, pv);
   });
   if (keep_all || ties_all_kept) return;
 
@@ -194,10 +233,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
   const int per = (V + kWarpThreads - 1) / kWarpThreads;
   const int lo = min(V, tid * per), hi = min(V, lo + per);
   int cnt = 0;
-  for (int i = lo; i < hi; ++i) {
-    const float e = warp_e(z[i], zmax, a.c);
-    cnt += e == e_thr;
-  }
+  for (int i = lo; i < hi; ++i) cnt += warp_e(z[i], zmax, a.c) == e_thr;
   int incl = cnt;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
@@ -226,6 +262,8 @@ extern "C" int bass_warp_probs(int32_t R, int32_t V, const float* logits, float 
   if (!(temperature > 0.f) || !(top_p > 0.f)) return BASS_ERR_INVALID_ARG;
   if (V > kWarpMaxVocab) return BASS_ERR_UNSUPPORTED;
   WarpParams a{R, V, logits, probs, (float)(1.4426950408889634 / (double)temperature), top_p, dev_status};
-  hipLaunchKernelGGL(warp_probs_kernel, dim3((unsigned)R), dim3(kWarpThreads), 0, (hipStream_t)stream, a);
+  const bool wide = V % 4 == 0 && (((uintptr_t)logits | (uintptr_t)probs) & 15) == 0;  // rows 16-byte aligned
+  if (wide) hipLaunchKernelGGL(warp_probs_kernel<4>, dim3((unsigned)R), dim3(kWarpThreads), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(warp_probs_kernel<1>, dim3((unsigned)R), dim3(kWarpThreads), 0, (hipStream_t)stream, a);
   return launch_status();
 }
