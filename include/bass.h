@@ -252,7 +252,9 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
 /*
  * Tuning knob (host state, process wide): number of wavefronts the bf16/fp32 attention
  * kernel spreads the flattened (sequence, kv-head, context-block) work over.  Values are
- * clamped to [64, 8192]; 0 restores the default.  Returns the value in effect.
+ * clamped to [64, 8192]; 0 restores the default.  Returns the value in effect.  (bf16 caches with
+ * more than 16 query rows per kv head use workgroups of four wavefronts: a setting W gives W / 2
+ * workgroups there.)
  */
 int bass_set_attention_waves(int waves);
 

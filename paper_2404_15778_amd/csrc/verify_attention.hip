@@ -30,6 +30,7 @@
 // for two 16-token tiles, exactly the operand layout of the second once the V block is
 // stored in that token order, so P goes from accumulator to operand with a bf16 pack only.
 // Query rows of one kv head are (draft i, head-in-group) pairs, up to 64 rows = 4 tiles.
+#include <algorithm>
 #include <cstdio>
 #include <type_traits>
 #include <cstdlib>
@@ -70,6 +71,7 @@ static int attention_waves(bool many_rows = false, bool int8 = false) {
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
   int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
+  int nshares;  // stretches the block list is cut into: one per wavefront, or one per workgroup (tile kernel)
   int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
   int span;  // BASS-PAD variant: every active sequence is processed over at least this many cache
              // positions (0: over its own length); the positions beyond its length are masked
@@ -457,8 +459,8 @@ __device__ inline void arrive(const AttnParams& p, const Split& sp, int lane, Co
 // Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
 // They belong to no wavefront's share of blocks, so wavefront w clears them for the units
 // w, w + nwaves, ... right at the start, off the critical path.
-__device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int lane) {
-  for (int unit = w; unit < p.B * p.Hkv; unit += p.nwaves) {
+__device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int nw, int lane) {
+  for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
     const int b = unit / p.Hkv;
     int nq;
     if (b < 64) {
@@ -854,11 +856,12 @@ struct QFrag {
 };
 
 template <int D, int NT>
-__device__ inline void load_queries(const AttnParams& p, const Unit& u, bool enable, int col, int grp, QFrag<D, NT>& f) {
+__device__ inline void load_queries(const AttnParams& p, const Unit& u, bool enable, int col, int grp, QFrag<D, NT>& f,
+                                    int row0 = 0) {
   const int rows = u.nq * p.g;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const int rrow = nt * 16 + col;
+    const int rrow = row0 + nt * 16 + col;  // row0: first query row of this wavefront (tile kernel)
     const bool ok = enable && rrow < rows;
     const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
     f.lim[nt] = u.L + i;
@@ -886,7 +889,8 @@ __device__ inline void clear_state(RowState<D, NT>& st) {
 // Partial of (wavefront w, unit u): slot ids w + unit are unique because both grow monotonically
 // along the flattened list.
 template <int D, int NT>
-__device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, const RowState<D, NT>& st, int col, int grp) {
+__device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, const RowState<D, NT>& st, int col, int grp,
+                                     int row0 = 0) {
   const int rows = u.nq * p.g;
   const size_t slot = (size_t)w + (size_t)u.b * p.Hkv + u.kvh;
   const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot * p.rows_max * D, (unsigned)p.rows_max * D * 4);
@@ -895,7 +899,7 @@ __device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, 
     float l = st.l[nt];
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
-    const int rrow = nt * 16 + col;
+    const int rrow = row0 + nt * 16 + col;
     if (rrow < rows) {
       const unsigned off = (unsigned)(rrow * D + 4 * grp) * 4;
 #pragma unroll
@@ -923,10 +927,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 
   const Sched sched = make_sched(p, lane, w == 0);
   const int total = sched.total * p.Hkv;
-  const Split sp = make_split(total, p.nwaves);
+  const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
-  zero_unused_rows(p, sched, w, lane);
+  zero_unused_rows(p, sched, w, p.nwaves, lane);
   BASS_TRACE(1);
 
   while (x < x_end) {
@@ -1108,6 +1112,104 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Workgroup-level kernel for kv heads with more than 16 query rows (grouped-query attention), bf16.
+// The accumulators of two to four 16-row tiles in ONE wavefront leave registers for a single block in
+// flight, and re-reading blocks by several wavefronts crosses the fabric twice.  Here a workgroup of
+// four wavefronts takes a stretch of the block list together: every K/V block is fetched from memory
+// once (each wavefront a quarter of it, three blocks ahead), put into a two-slot ring in LDS, and
+// read from there by the wavefronts that own a query tile (wavefront t: rows 16 t .. 16 t + 15), each
+// running the one-tile block step.  A wavefront needs < 256 registers, so two workgroups share a
+// compute unit.  One barrier per block: a slot is rewritten only after the barrier that follows the
+// last step that read it.  Every barrier sits in workgroup-uniform control flow (the stretch, the
+// units and the block counts depend on the workgroup index and the lengths only).
+// ---------------------------------------------------------------------------------------
+constexpr int kTileAhead = 3;  // blocks a workgroup has in flight from memory (measured best: 3)
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
+  constexpr int kBlkVec = kBlockTokens * D * 2 / 16;  // uint4 per block and tensor
+  constexpr int kQuarter = kBlkVec / 4;                // uint4 a wavefront moves per block and tensor
+  constexpr int kLoads = kQuarter / 64;                // 16-byte loads per lane, block and tensor
+  __shared__ uint4 ring_k[2][kBlkVec];
+  __shared__ uint4 ring_v[2][kBlkVec];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int col = lane & 15, grp = lane >> 4;
+  const int wg = blockIdx.x;  // the stretch of this workgroup
+  const int row0 = 16 * wv;
+
+  const Sched sched = make_sched(p, lane, wg == 0 && wv == 0);
+  const int total = sched.total * p.Hkv;
+  const Split sp = make_split(total, p.nshares);
+  int x = sp.first(wg);
+  const int x_end = sp.first(wg + 1);
+  zero_unused_rows(p, sched, wg * 4 + wv, 4 * p.nshares, lane);
+
+  const uint4* kc = (const uint4*)p.Kc;
+  const uint4* vc = (const uint4*)p.Vc;
+  struct Stage {
+    uint4 k[kLoads], v[kLoads];
+  };
+
+  while (x < x_end) {
+    const Unit u = locate(p, sched, x, lane);
+    const int span = min(x_end, u.begin + u.nblk + p.pad) - x;  // our stretch of the unit, virtual blocks included
+    const int n = min(span, u.begin + u.nblk - x);               // its real blocks
+    if (n <= 0) {
+      x += span;
+      continue;
+    }
+    const bool active = row0 < u.nq * p.g;  // this wavefront owns a query tile of the unit
+    QFrag<D, 1> q;
+    load_queries<D, 1>(p, u, active, col, grp, q, row0);
+    RowState<D, 1> st;
+    clear_state<D, 1>(st);
+    const int blk0 = x - u.begin;
+    const ptrdiff_t vec0 = (((ptrdiff_t)u.b * p.Hkv + u.kvh) * p.nblk_cap + blk0) * kBlkVec;
+    const int mine = wv * kQuarter + lane;  // first uint4 this lane moves
+
+    // all fetches unconditional (exact wait counts); one past the end re-reads the stretch's first block
+    auto fetch = [&](Stage& g, int s) {
+      const ptrdiff_t off = vec0 + (s < n ? (ptrdiff_t)s * kBlkVec : 0) + mine;
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) g.k[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(kc + off + i * 64)));
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) g.v[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(vc + off + i * 64)));
+    };
+    // block s: own quarter into LDS, next fetch, barrier -- for every s, also past the end (the loads and
+    // the barrier stay outside all branches: a load under a branch costs a full wait at the join) --
+    // then, for real blocks, the one-tile step from LDS
+    auto step = [&](Stage& g, int s) {
+      const int slot = s & 1;
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        ring_k[slot][mine + i * 64] = g.k[i];
+        ring_v[slot][mine + i * 64] = g.v[i];
+      }
+      fetch(g, s + kTileAhead);
+      __syncthreads();
+      if (active && s < n) {
+        KvRegs<D> r;
+#pragma unroll
+        for (int i = 0; i < 2 * (D / 32); ++i) r.k[i] = ring_k[slot][i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) r.v[i] = ring_v[slot][i * 64 + lane];
+        block_dispatch<D, 1>(r, q.q, st, blk0 + s, u.L, u.L + u.nq, q.lim, p.scale_log2, lane, false, NewRows{}, nullptr, nullptr);
+      }
+    };
+    __syncthreads();  // the previous unit's last step has left the ring
+    Stage g[kTileAhead];
+#pragma unroll
+    for (int j = 0; j < kTileAhead; ++j) fetch(g[j], j);
+    for (int s = 0; s < n; s += kTileAhead) {  // workgroup-uniform trip count
+#pragma unroll
+      for (int j = 0; j < kTileAhead; ++j) step(g[j], s + j);
+    }
+    if (active) store_partial<D, 1>(p, u, wg, st, col, grp, row0);
+    x += span;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Split-context reduction as a launch of its own, used when a kv head has many query rows
 // (grouped-query attention): a unit's partials are then tens of KiB per contributor, too much
 // for the one wavefront that happens to arrive last, so the rows are spread over the whole chip:
@@ -1149,7 +1251,7 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   }
   CombineJob job;
   job.u = Unit{b, kvh, L, nq, nb - p.pad, before * p.Hkv + kvh * nb};
-  const Split sp = make_split(sched.total * p.Hkv, p.nwaves);
+  const Split sp = make_split(sched.total * p.Hkv, p.nshares);
   job.w_lo = sp.owner(job.u.begin);
   job.w_hi = sp.owner(job.u.begin + job.u.nblk - 1);
   CombineRegs<KC> regs;
@@ -1172,10 +1274,10 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
 
   const Sched sched = make_sched(p, lane, w == 0);
   const int total = sched.total * p.Hkv;
-  const Split sp = make_split(total, p.nwaves);
+  const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
-  zero_unused_rows(p, sched, w, lane);
+  zero_unused_rows(p, sched, w, p.nwaves, lane);
 
   while (x < x_end) {
     const Unit u = locate(p, sched, x, lane);
@@ -1349,6 +1451,11 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
+  // bf16 caches, more than one query tile per kv head: the workgroup-level kernel, one stretch per
+  // workgroup (default 256, measured best: fewer partials to merge; a wavefront setting W gives W / 2)
+  // (it has no fused append: bass_append_verify_attention keeps the wavefront-level kernel)
+  const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16 && !K_new;
+  p.nshares = !tiles ? p.nwaves : g_attention_waves > 0 ? std::max(16, p.nwaves / 2) : 256;
   p.pad = K_new ? g_append_pad : g_plain_pad;
   p.span = span;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
@@ -1370,6 +1477,9 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   const dim3 grid(p.nwaves / p.wpw), block(64 * p.wpw);
   if (d->dtype == BASS_DTYPE_FP32) {
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
+  } else if (tiles) {
+    if (d->D == 128) hipLaunchKernelGGL(verify_attn_tiles_bf16<128>, dim3((unsigned)p.nshares), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(verify_attn_tiles_bf16<64>, dim3((unsigned)p.nshares), dim3(256), 0, s, p);
   } else {
     const int nt = (rows_max + 15) / 16;
     // LDS slice per wavefront of a fused append: K and V rows of two units (bf16, or INT8 codes + scales)
@@ -1386,7 +1496,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
         if (nt == 1) BASS_LAUNCH_I8(64, 1); else if (nt == 2) BASS_LAUNCH_I8(64, 2);
         else if (nt == 3) BASS_LAUNCH_I8(64, 3); else BASS_LAUNCH_I8(64, 4);
       }
-    } else if (d->D == 128) {
+    } else if (d->D == 128) {  // bf16: more than one tile only with a fused append (else the workgroup-level kernel above)
       if (nt == 1) BASS_LAUNCH(128, 1); else if (nt == 2) BASS_LAUNCH(128, 2);
       else if (nt == 3) BASS_LAUNCH(128, 3); else BASS_LAUNCH(128, 4);
     } else {
