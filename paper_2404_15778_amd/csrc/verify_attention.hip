@@ -941,6 +941,14 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       x += spanA;
       continue;
     }
+    // the share's first block is fetched right away; what follows (the second unit, the queries, the
+    // rows of a fused append, ...) runs while that fetch is under way
+    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + (x - uA.begin)) * kBlkVec;
+    const uint4* kc = (const uint4*)p.Kc;
+    const uint4* vc = (const uint4*)p.Vc;
+    Regs r0;
+    if constexpr (kI8) load_block_i8<D>(r0, kc + vecA, vc + vecA, lane, grp);
+    else load_block<D>(r0, kc + vecA + lane, vc + vecA + lane);
     Unit uB = uA;
     int nB = 0, spanB = 0;
     bool hasB = false;
@@ -1002,10 +1010,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     };
 
     // element offsets (in uint4) of step s inside the K and V caches
-    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + (x - uA.begin)) * kBlkVec;
     const ptrdiff_t vecB = (((ptrdiff_t)uB.b * p.Hkv + uB.kvh) * p.nblk_cap - nA) * kBlkVec;
-    const uint4* kc = (const uint4*)p.Kc;
-    const uint4* vc = (const uint4*)p.Vc;
 
     // Every fetch is issued unconditionally so that the wait counts before each compute step are
     // exact (a fetch under a branch would force a wait for ALL outstanding loads at the join and
@@ -1054,8 +1059,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     };
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
-      Regs r0, r1, r2;
-      fetch(r0, 0);
+      Regs r1, r2;  // r0 is on its way already
       fetch(r1, 1);
       if (stage1) {
         commit(u1, 0, sr, new1);  // these loads were issued before the fetches
@@ -1071,8 +1075,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       }
     } else {
       // many query rows need the registers for accumulators: two-deep ring
-      Regs r0, r1;
-      fetch(r0, 0);
+      Regs r1;
       if (stage1) {
         commit(u1, 0, sr, new1);
         stage_rest();
