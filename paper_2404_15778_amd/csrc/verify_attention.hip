@@ -98,13 +98,24 @@ struct AttnParams {
 // ---------------------------------------------------------------------------------------
 // Flattened schedule, recomputed by every wavefront from the device-side lengths.
 // ---------------------------------------------------------------------------------------
+// Inclusive prefix sum over the wavefront.  Shifts inside rows of 16 lanes are DPP moves (a few cycles
+// each; a generic shuffle goes through the LDS crossbar, ~100 cycles, and this scan sits on the path
+// from launch to the first K/V load); the three row totals are then added from scalar registers.
+template <int N>
+__device__ inline int row_shift_right(int v) {  // lane i of a row gets lane i - N of the row, 0 for i < N
+  return __builtin_amdgcn_update_dpp(0, v, 0x110 + N, 0xF, 0xF, true);
+}
+
 __device__ inline int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(v, d);
-    if (lane >= d) v += o;
-  }
-  return v;
+  v += row_shift_right<1>(v);
+  v += row_shift_right<2>(v);
+  v += row_shift_right<4>(v);
+  v += row_shift_right<8>(v);
+  const int t0 = __builtin_amdgcn_readlane(v, 15);
+  const int t1 = __builtin_amdgcn_readlane(v, 31);
+  const int t2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane >> 4;
+  return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
 }
 
 // Length of a unit in the flattened list = its real blocks plus p.pad virtual ones at its end.
