@@ -251,13 +251,16 @@ __device__ inline float2 load_dev(const float* src) {
 //   M = max_s m_s ;  l = sum_s l_s 2^(m_s - M) ;  O = sum_s acc_s 2^(m_s - M) / l
 // over the partials of wavefronts w_lo..w_hi, then zeros for the unit's unused query slots.
 // ---------------------------------------------------------------------------------------
+// DC: the head size when it is known at compile time (the divisions below then cost nothing; this code
+// runs before a wavefront's first K/V load), 0: read it from the descriptor.
+template <int DC>
 __device__ inline void zero_rows(const AttnParams& p, int b, int kvh, int row_from, int lane) {
-  const int D = p.D, lpr = D / 4, rpi = 64 / lpr;
+  const int D = DC ? DC : p.D, lpr = D / 4, rpi = 64 / lpr;
   const int rows_all = p.kmax * p.g;
   for (int r0 = row_from; r0 < rows_all; r0 += rpi) {
     const int r = r0 + lane / lpr;
     if (lane < rpi * lpr && r < rows_all) {
-      const int i = r / p.g, hg = r % p.g;
+      const int i = r / p.g, hg = r - i * p.g;
       const size_t orow = ((size_t)b * p.kmax + i) * p.Hq + kvh * p.g + hg;
       *(float4*)(p.O + orow * D + (lane % lpr) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
       if (p.lse && lane % lpr == 0) p.lse[orow] = 0.f;
@@ -470,6 +473,7 @@ __device__ inline void arrive(const AttnParams& p, const Split& sp, int lane, Co
 // Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
 // They belong to no wavefront's share of blocks, so wavefront w clears them for the units
 // w, w + nwaves, ... right at the start, off the critical path.
+template <int DC>
 __device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int nw, int lane) {
   for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
     const int b = unit / p.Hkv;
@@ -481,7 +485,7 @@ __device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int
       bool bad;
       seq_blocks(p, b, L, nq, bad);
     }
-    zero_rows(p, b, unit % p.Hkv, nq * p.g, lane);
+    zero_rows<DC>(p, b, unit - b * p.Hkv, nq * p.g, lane);
   }
 }
 
@@ -941,7 +945,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
-  zero_unused_rows(p, sched, w, p.nwaves, lane);
+  zero_unused_rows<D>(p, sched, w, p.nwaves, lane);
   BASS_TRACE(1);
 
   while (x < x_end) {
@@ -1156,7 +1160,7 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(wg);
   const int x_end = sp.first(wg + 1);
-  zero_unused_rows(p, sched, wg * 4 + wv, 4 * p.nshares, lane);
+  zero_unused_rows<D>(p, sched, wg * 4 + wv, 4 * p.nshares, lane);
 
   const uint4* kc = (const uint4*)p.Kc;
   const uint4* vc = (const uint4*)p.Vc;
@@ -1291,7 +1295,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
-  zero_unused_rows(p, sched, w, p.nwaves, lane);
+  zero_unused_rows<0>(p, sched, w, p.nwaves, lane);
 
   while (x < x_end) {
     const Unit u = locate(p, sched, x, lane);
