@@ -173,3 +173,33 @@ def test_pad_and_split_launch_variants_match_the_oracle(hip, dtype, D, variant):
         assert np.isfinite(O).all() and np.isfinite(lse).all()
         assert np.abs(O - Or).max() <= TOL[dtype]
         assert np.abs(lse - lser).max() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,kmax", [(128, 16, 2, 6), (64, 8, 1, 8), (128, 6, 2, 6), (128, 16, 4, 8)])
+@pytest.mark.parametrize("waves", [0, 64, 200, 8192])
+def test_grouped_query_shapes_over_work_spreads_and_variants(hip, D, Hq, Hkv, kmax, waves):
+    # 48, 64, 18 and 32 query rows per kv head: the workgroup-level kernel (one 16-row tile per wavefront) with
+    # few and many workgroups, units shorter than a workgroup's stretch and longer, and the PAD / SPLIT variants
+    import torch
+    import paper_2404_15778_amd as bass
+    ctx = [700, 31, 0, 333, 64, 1]
+    nq = [kmax, 1, 2, kmax - 1, 0, kmax]
+    w = wl.make_attention("gqa_tiles", 6, Hq, Hkv, D, "bf16", ctx, nq, 29, kmax=kmax, Lcap=720)
+    Or, lser = oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale)
+    _, _, _, da = hip.run_attention_workload(w, poison=True)
+    Q, c, n = hip.to_device(w.Q), hip.i32(w.ctx_len), hip.i32(w.draft_len)
+    longest = int((w.ctx_len + w.draft_len).max())
+    bass.bass_set_attention_waves(waves)
+    try:
+        for variant in ("ragged", "pad", "split"):
+            da.O.fill_(float("nan"))
+            da.lse.fill_(float("nan"))
+            O, lse = da.verify(Q, c, n, variant=variant, padded_len=longest)
+            torch.cuda.synchronize()
+            O, lse = hip.to_host(O), hip.to_host(lse)
+            assert int(da.status.item()) == 0
+            assert np.isfinite(O).all() and np.isfinite(lse).all()
+            assert np.abs(O - Or).max() <= TOL["bf16"], variant
+            assert np.abs(lse - lser).max() <= TOL["bf16"], variant
+    finally:
+        bass.bass_set_attention_waves(0)
