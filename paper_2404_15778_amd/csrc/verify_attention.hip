@@ -1143,7 +1143,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
 // ---------------------------------------------------------------------------------------
 constexpr int kTileAhead = 3;  // blocks a workgroup has in flight from memory (measured best: 3)
 
-template <int D>
+template <int D, bool kFused>
 __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
   constexpr int kBlkVec = kBlockTokens * D * 2 / 16;  // uint4 per block and tensor
   constexpr int kQuarter = kBlkVec / 4;                // uint4 a wavefront moves per block and tensor
@@ -1204,7 +1204,43 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
         ring_v[slot][mine + i * 64] = g.v[i];
       }
       fetch(g, s + kTileAhead);
-      __syncthreads();
+      // Fused append: a block that holds new tokens is patched in LDS once it is complete there (K: the
+      // 16-byte chunks of the new rows; V: their elements, 2 bytes each), and the patched chunks go into the
+      // cache from LDS as whole 16-byte chunks.  The test is workgroup-uniform; the loads of the new rows
+      // sit under this branch and cost a full wait, in these one or two blocks per unit only.
+      const int tok0 = (blk0 + s) * kBlockTokens;
+      if (kFused && s < n && u.nq > 0 && tok0 < u.L + u.nq && tok0 + kBlockTokens > u.L) {
+        __syncthreads();  // the block is complete in LDS
+        const int i_hi = min(u.nq, tok0 + kBlockTokens - u.L);
+        for (int i = max(0, tok0 - u.L) + wv; i < i_hi; i += 4) {  // new rows of this block, one per wavefront and turn
+          const int tw = u.L + i - tok0;                              // its token slot in the block
+          if (lane < D / 8) {                                         // one 16-byte chunk of the row per lane
+            const size_t src = (((size_t)u.b * p.kmax + i) * p.Hkv + u.kvh) * D + 8 * lane;
+            const uint4 kv = *(const uint4*)((const uint16_t*)p.Knew + src);
+            const uint4 vv = *(const uint4*)((const uint16_t*)p.Vnew + src);
+            const size_t ko = k_elem_offset(D, tw, 8 * lane) / 8;  // in 16-byte chunks
+            ring_k[slot][ko] = kv;
+            ((uint4*)const_cast<void*>(p.Kc))[vec0 + (ptrdiff_t)s * kBlkVec + (ptrdiff_t)ko] = kv;
+            const uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              ((uint16_t*)&ring_v[slot][0])[v_elem_offset(D, tw, 8 * lane + e)] = (uint16_t)(vw[e >> 1] >> (16 * (e & 1)));
+          }
+        }
+        __syncthreads();  // the patches are visible
+        for (int c = threadIdx.x; c < (D / 16) * 64; c += 256) {  // V chunks that hold a new token: back into the cache
+          const int cg = (c & 63) >> 4;
+          bool any = false;
+#pragma unroll
+          for (int jj = 0; jj < 8; ++jj) {
+            const int t = tok0 + (jj < 4 ? 4 * cg + jj : 16 + 4 * cg + (jj - 4));
+            any |= t >= u.L && t < u.L + u.nq;
+          }
+          if (any) ((uint4*)const_cast<void*>(p.Vc))[vec0 + (ptrdiff_t)s * kBlkVec + c] = ring_v[slot][c];
+        }
+      } else {
+        __syncthreads();
+      }
       if (active && s < n) {
         KvRegs<D> r;
 #pragma unroll
@@ -1471,8 +1507,7 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
   // bf16 caches, more than one query tile per kv head: the workgroup-level kernel, one stretch per
   // workgroup (default 256, measured best: fewer partials to merge; a wavefront setting W gives W / 2)
-  // (it has no fused append: bass_append_verify_attention keeps the wavefront-level kernel)
-  const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16 && !K_new;
+  const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16;
   p.nshares = !tiles ? p.nwaves : g_attention_waves > 0 ? std::max(16, p.nwaves / 2) : 256;
   p.pad = K_new ? g_append_pad : g_plain_pad;
   p.span = span;
@@ -1496,8 +1531,14 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   if (d->dtype == BASS_DTYPE_FP32) {
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
   } else if (tiles) {
-    if (d->D == 128) hipLaunchKernelGGL(verify_attn_tiles_bf16<128>, dim3((unsigned)p.nshares), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(verify_attn_tiles_bf16<64>, dim3((unsigned)p.nshares), dim3(256), 0, s, p);
+    const dim3 tgrid((unsigned)p.nshares), tblock(256);
+    if (d->D == 128) {
+      if (K_new) hipLaunchKernelGGL((verify_attn_tiles_bf16<128, true>), tgrid, tblock, 0, s, p);
+      else hipLaunchKernelGGL((verify_attn_tiles_bf16<128, false>), tgrid, tblock, 0, s, p);
+    } else {
+      if (K_new) hipLaunchKernelGGL((verify_attn_tiles_bf16<64, true>), tgrid, tblock, 0, s, p);
+      else hipLaunchKernelGGL((verify_attn_tiles_bf16<64, false>), tgrid, tblock, 0, s, p);
+    }
   } else {
     const int nt = (rows_max + 15) / 16;
     // LDS slice per wavefront of a fused append: K and V rows of two units (bf16, or INT8 codes + scales)
@@ -1514,12 +1555,10 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
         if (nt == 1) BASS_LAUNCH_I8(64, 1); else if (nt == 2) BASS_LAUNCH_I8(64, 2);
         else if (nt == 3) BASS_LAUNCH_I8(64, 3); else BASS_LAUNCH_I8(64, 4);
       }
-    } else if (d->D == 128) {  // bf16: more than one tile only with a fused append (else the workgroup-level kernel above)
-      if (nt == 1) BASS_LAUNCH(128, 1); else if (nt == 2) BASS_LAUNCH(128, 2);
-      else if (nt == 3) BASS_LAUNCH(128, 3); else BASS_LAUNCH(128, 4);
+    } else if (d->D == 128) {  // bf16, one query tile (more tiles: the workgroup-level kernel above)
+      BASS_LAUNCH(128, 1);
     } else {
-      if (nt == 1) BASS_LAUNCH(64, 1); else if (nt == 2) BASS_LAUNCH(64, 2);
-      else if (nt == 3) BASS_LAUNCH(64, 3); else BASS_LAUNCH(64, 4);
+      BASS_LAUNCH(64, 1);
     }
 #undef BASS_LAUNCH_I8
 #undef BASS_LAUNCH
