@@ -515,6 +515,26 @@ struct TokenScales {
   float k[8], v[8];
 };
 
+// Reductions over the four lanes l, l + 16, l + 32, l + 48 (the lanes that share a query row in the
+// matrix-core result layout) with gfx950's lane-swap instructions: v_permlane32_swap of a value with
+// itself leaves (low half, low half) and (high half, high half), v_permlane16_swap (rows 0 and 2 twice)
+// and (rows 1 and 3 twice) -- two VALU operations per step instead of two trips through the LDS crossbar.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline float rows4_max(float v) {
+  const u32x2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const u32x2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+__device__ inline float rows4_sum(float v) {
+  const u32x2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const u32x2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // INT8 caches: a block's codes (two fragments per 16-byte chunk) and the scales of this lane's tokens.
 template <int D>
 struct KvRegsI8 {
@@ -808,8 +828,7 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
       }
     }
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = rows4_max(mx);
     const float m_new = fmaxf(st.m[nt], mx);
     // a row that has seen no visible token yet keeps m = -inf; subtract 0 instead so that
     // exp2(-inf - 0) = 0 and no inf - inf appears
@@ -912,8 +931,7 @@ __device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, 
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     float l = st.l[nt];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    l = rows4_sum(l);
     const int rrow = row0 + nt * 16 + col;
     if (rrow < rows) {
       const unsigned off = (unsigned)(rrow * D + 4 * grp) * 4;
