@@ -235,7 +235,7 @@ def main():
                         f"ctx U[512,2048], drafts U[1,6]) x {NL} layers + spec_accept (V=50000, k=5)",
             "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "layers": NL, "seed": args.seed,
             "ctx_len": w.ctx_len.tolist(), "draft_len": w.draft_len.tolist(),
-            "kv_bytes_per_layer": kv_bytes, "attention_waves": bass.bass_set_attention_waves(args.waves),
+            "kv_bytes_per_layer": kv_bytes, "attention_waves": args.waves if args.waves else ("library default (1024)" if args.kv_int8 else bass.bass_set_attention_waves(0)),
             "launch": "eager" if args.no_graph else "hip_graph_replay",
             "append": "separate launch" if args.separate_append else "fused into the attention launch",
         },

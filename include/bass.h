@@ -44,10 +44,13 @@ enum {
 };
 
 /* BASS_DTYPE_INT8KV: Q, K_new, V_new are bf16; the caches hold INT8 codes with one fp32 scale per
- * token and kv head (the paper's appendix: dynamic per-head and per-token quantization of keys and
- * values).  Symmetric: amax = max_d |x_d|, code_d = rint(x_d * (127 / amax)) (one fp32 division, one
- * fp32 product, round half to even), scale = amax / 127; a row of zeros has scale 0.  The attention
- * runs over the represented values code * scale. */
+ * token and kv head (the paper's appendix: dynamic per-head and per-token quantization of keys,
+ * queries and values, the granularity of the inner-product dimension, so that the score product runs
+ * in integer arithmetic).  Symmetric: amax = max_d |x_d|, code_d = rint(x_d * (127 / amax)) (one fp32
+ * division, one fp32 product, round half to even), scale = amax / 127; a row of zeros has scale 0.
+ * The attention kernels quantize every query row (one token, one query head) the same way on the fly;
+ * the scores are the exact integer products of query and key codes times both scales, and the whole
+ * attention is the one over the represented values code * scale of queries, keys and values. */
 enum { BASS_DTYPE_BF16 = 0, BASS_DTYPE_FP32 = 1, BASS_DTYPE_INT8KV = 2 };
 
 /* Shape of one attention layer's verification call. */
@@ -252,9 +255,10 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
 /*
  * Tuning knob (host state, process wide): number of wavefronts the bf16/fp32 attention
  * kernel spreads the flattened (sequence, kv-head, context-block) work over.  Values are
- * clamped to [64, 8192]; 0 restores the default.  Returns the value in effect.  (bf16 caches with
- * more than 16 query rows per kv head use workgroups of four wavefronts: a setting W gives W / 2
- * workgroups there.)
+ * clamped to [64, 8192]; 0 restores the defaults, which depend on the call: 768 for bf16 / fp32 with up
+ * to 16 query rows per kv head, 1024 for INT8 caches, 256 workgroups of four wavefronts for bf16 caches
+ * with more query rows (a setting W gives W / 2 workgroups there).  Returns the value in effect for
+ * the first of these cases.
  */
 int bass_set_attention_waves(int waves);
 

@@ -1,8 +1,8 @@
 """Oracle for the INT8 KV cache.  TEST INFRASTRUCTURE ONLY.
 
-The paper's appendix (quantization schemes): keys and values are quantized dynamically per head
-and per token, i.e. one range per row of D head elements -- the inner-product dimension of the
-score product.  Reading taken here (the paper gives the granularity, not the formula): symmetric
+The paper's appendix (quantization schemes): keys, queries and values are quantized dynamically
+per head and per token, i.e. one range per row of D head elements -- the inner-product dimension
+of the score product, which can then be taken in integer arithmetic.  Reading taken here (the paper gives the granularity, not the formula): symmetric
 INT8 with the row's largest magnitude mapped to 127,
 
     amax = max_d |x_d|          (x: the bf16 row the model produced, exact in fp32)
@@ -12,7 +12,8 @@ INT8 with the row's largest magnitude mapped to 127,
 
 Every step is a single IEEE fp32 operation, so an implementation that takes the same steps gets
 the same codes and scales bit for bit.  The attention over an INT8 cache is the plain ragged
-attention over the represented values code * s (oracle.verify_attention on fp32 inputs).
+attention over the represented values code * s of the queries (quantized per token and query
+head), keys and values (oracle.verify_attention on fp32 inputs).
 """
 from __future__ import annotations
 

@@ -1,7 +1,7 @@
 // Version and status strings of libbass, and the host-side draft-length heuristic.
 #include "bass_common.h"
 
-extern "C" int bass_version(void) { return 120; /* 0.1.20: + PAD/SPLIT variants, logits front end, INT8 caches */ }
+extern "C" int bass_version(void) { return 121; /* 0.1.21: INT8 caches in the operand order of the integer score product */ }
 
 extern "C" const char* bass_status_string(int code) {
   switch (code) {

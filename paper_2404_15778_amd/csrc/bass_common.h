@@ -44,20 +44,20 @@ __host__ __device__ inline size_t v_elem_offset(int /*D*/, int tok_in_blk, int d
 }
 
 // ---------------------------------------------------------------------------------------
-// INT8 cache layout (BASS_DTYPE_INT8KV).  Same blocks of 32 tokens; a block holds the 32*D codes
-// in the element order of the bf16 layout above -- fragment f (K: f = tt*(D/32) + t, V: f = mt) of a
-// lane is 8 codes = 8 bytes -- with two consecutive fragments packed into a lane's 16-byte chunk so
-// that a wavefront still reads 1 KiB per load instruction:
-//   byte offset of code j of fragment f of a lane = ((f/2)*64 + lane)*16 + (f%2)*8 + j
-// followed by the block's 32 fp32 scales in token order (one per token of this kv head).
+// INT8 cache layout (BASS_DTYPE_INT8KV).  Same blocks of 32 tokens; a block holds the 32*D codes as
+// 16-byte chunks per lane, so that a wavefront still reads 1 KiB per load instruction, followed by the
+// block's 32 fp32 scales in token order (one per token of this kv head).
+//   K block: [tile tt (2)][k-step ks (D/64)][lane (64)][j (16)] -- the operand order of the INT8 matrix
+//            instruction (16x16x64): lane = grp*16 + r holds token 16*tt + r, head elements 64*ks + 16*grp + j
+//   V block: the element order of the bf16 V layout above, fragment mt of a lane being 8 codes = 8 bytes,
+//            two consecutive fragments per chunk: byte ((mt/2)*64 + lane)*16 + (mt%2)*8 + j
 // ---------------------------------------------------------------------------------------
 __host__ __device__ inline size_t i8_block_bytes(int D) { return (size_t)kBlockTokens * D + kBlockTokens * 4; }
 
 __host__ __device__ inline size_t i8_k_offset(int D, int tok_in_blk, int d) {
   const int tt = tok_in_blk >> 4, r = tok_in_blk & 15;
-  const int t = d >> 5, grp = (d & 31) >> 3, j = d & 7;
-  const int f = tt * (D >> 5) + t, lane = grp * 16 + r;
-  return (size_t)(((f >> 1) * 64 + lane) * 16 + (f & 1) * 8 + j);
+  const int ks = d >> 6, grp = (d & 63) >> 4, j = d & 15;
+  return (size_t)(((tt * (D >> 6) + ks) * 64 + grp * 16 + r) * 16 + j);
 }
 
 __host__ __device__ inline size_t i8_v_offset(int /*D*/, int tok_in_blk, int d) {

@@ -42,6 +42,7 @@ namespace bass {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 static int g_attention_waves = 0;  // 0 = default
 static int g_append_pad = 3;      // virtual blocks per unit when the append is fused (measured best: 3)
@@ -535,7 +536,8 @@ __device__ inline float rows4_sum(float v) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// INT8 caches: a block's codes (two fragments per 16-byte chunk) and the scales of this lane's tokens.
+// INT8 caches: a block's codes and the scales of this lane's tokens.  k[tt * (D/64) + ks]: the 16 codes of
+// token 16 tt + lane % 16, head elements 64 ks + 16 grp ..; v[m]: V fragments 2m and 2m + 1 (8 codes each).
 template <int D>
 struct KvRegsI8 {
   u32x4 k[D / 32], v[D / 32];
@@ -565,10 +567,9 @@ __device__ inline uint4 codes_to_bf16(uint32_t lo, uint32_t hi) {
   return __builtin_bit_cast(uint4, o);
 }
 
+// V codes -> bf16 fragments (the K codes go to the INT8 matrix instruction as they are) and the scales
 template <int D>
 __device__ inline void dequant_block(const KvRegsI8<D>& q, KvRegs<D>& r, TokenScales& sc) {
-#pragma unroll
-  for (int f = 0; f < 2 * (D / 32); ++f) r.k[f] = codes_to_bf16(q.k[f >> 1][2 * (f & 1)], q.k[f >> 1][2 * (f & 1) + 1]);
 #pragma unroll
   for (int f = 0; f < D / 16; ++f) r.v[f] = codes_to_bf16(q.v[f >> 1][2 * (f & 1)], q.v[f >> 1][2 * (f & 1) + 1]);
 #pragma unroll
@@ -677,20 +678,18 @@ __device__ inline void stage_commit_i8(const Unit& u, int c0, int lane, const St
 // widened) and write them into the cache block at kblk / vblk (first byte of the block).
 template <int D>
 __device__ inline void patch_block_i8(KvRegsI8<D>& q, int tok0, const NewRows nr, int lane, uint8_t* kblk, uint8_t* vblk) {
-  constexpr int KS = D / 32, MT = D / 16;
+  constexpr int KS = D / 64, MT = D / 16;
   const int dr = lane & 15, grp = lane >> 4;
-  // K: fragment f = tl * KS + t of a lane is token 16 tl + lane % 16, head elements 32 t + 8 grp .. + 7
+  // K: chunk tl * KS + ks of a lane is token 16 tl + lane % 16, head elements 64 ks + 16 grp .. + 15
 #pragma unroll
   for (int tl = 0; tl < 2; ++tl) {
     const int i = tok0 + 16 * tl + dr - nr.L;
     if (i >= 0 && i < nr.nq) {
 #pragma unroll
-      for (int t = 0; t < KS; ++t) {
-        const int f = tl * KS + t;
-        const uint2 c = *(const uint2*)&new_rows_lds[nr.k_off + i * D + 32 * t + 8 * grp];
-        q.k[f >> 1][2 * (f & 1)] = c.x;
-        q.k[f >> 1][2 * (f & 1) + 1] = c.y;
-        *(uint2*)(kblk + ((f >> 1) * 64 + lane) * 16 + (f & 1) * 8) = c;
+      for (int ks = 0; ks < KS; ++ks) {
+        const u32x4 c = *(const u32x4*)&new_rows_lds[nr.k_off + i * D + 64 * ks + 16 * grp];
+        q.k[tl * KS + ks] = c;
+        *(u32x4*)(kblk + ((tl * KS + ks) * 64 + lane) * 16) = c;
       }
     }
   }
@@ -735,21 +734,31 @@ struct RowState {
 
 // One 32-token block against all query tiles.  kMasked: the block reaches beyond ctx_len, so
 // causal limits and the valid-token bound apply (wave-uniform choice).
+// INT8 caches: what the block step needs besides the widened V fragments -- the block's K codes, the
+// quantized queries and all the scales.
+template <int D, int NT>
+struct I8Operands {
+  const u32x4* k;                 // KvRegsI8::k of the block
+  const u32x4 (*q)[D / 64];       // query codes, B operand of the INT8 matrix instruction
+  const float* q_scale_log2;      // per tile: this lane's query-row scale * softmax scale * log2(e)
+  const TokenScales* sc;
+};
+
 template <int D, int NT, bool kMasked, bool kI8 = false>
 __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int tok0,
                                   int n_valid, const int (&lim)[NT], float scale_log2, int lane,
                                   bool fused = false, const NewRows& nr = NewRows{}, uint4* kdst = nullptr,
-                                  uint4* vdst = nullptr, const TokenScales* sc = nullptr) {
+                                  uint4* vdst = nullptr, const I8Operands<D, NT>* i8 = nullptr) {
   constexpr int KS = D / 32, MT = D / 16;
   const int grp = lane >> 4;
-  // INT8 caches: r holds the codes as bf16; a score is (q . codes) * k-scale, a value code * v-scale,
-  // the latter folded into the probabilities that multiply V.  Stale tokens may carry any scale.
-  float ksl[8], vsl[8];
+  // INT8 caches: a score is the integer product (q codes . k codes) * q-scale * k-scale, a value is
+  // code * v-scale, the latter folded into the probabilities that multiply V (r.v holds the codes as
+  // bf16).  Stale tokens may carry any scale.
+  float vsl[8];
   if (kI8) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      ksl[j] = sc->k[j] * scale_log2;
-      vsl[j] = sc->v[j];
+      vsl[j] = i8->sc->v[j];
       if (kMasked && tok0 + (j < 4 ? 4 * grp + j : 16 + 4 * grp + (j - 4)) >= n_valid) vsl[j] = 0.f;
     }
   }
@@ -808,17 +817,32 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
   }
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[t]), qf[nt][t], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[KS + t]), qf[nt][t], s1, 0, 0, 0);
-    }
     float s[8];
+    if constexpr (kI8) {
+      i32x4 a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      s[j] = s0[j] * (kI8 ? ksl[j] : scale_log2);
-      s[4 + j] = s1[j] * (kI8 ? ksl[4 + j] : scale_log2);
+      for (int ks = 0; ks < D / 64; ++ks) {
+        a0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, i8->k[ks]), __builtin_bit_cast(i32x4, i8->q[nt][ks]), a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, i8->k[D / 64 + ks]), __builtin_bit_cast(i32x4, i8->q[nt][ks]), a1, 0, 0, 0);
+      }
+      const float qs = i8->q_scale_log2[nt];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        s[j] = (float)a0[j] * (i8->sc->k[j] * qs);
+        s[4 + j] = (float)a1[j] * (i8->sc->k[4 + j] * qs);
+      }
+    } else {
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int t = 0; t < KS; ++t) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[t]), qf[nt][t], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[KS + t]), qf[nt][t], s1, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        s[j] = s0[j] * scale_log2;
+        s[4 + j] = s1[j] * scale_log2;
+      }
     }
     if (kMasked) {
 #pragma unroll
@@ -854,14 +878,14 @@ template <int D, int NT, bool kI8 = false>
 __device__ inline void block_dispatch(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], RowState<D, NT>& st, int blk,
                                       int L, int n_valid, const int (&lim)[NT], float scale_log2, int lane,
                                       bool fused, const NewRows& nr, uint4* kdst, uint4* vdst,
-                                      const TokenScales* sc = nullptr) {
+                                      const I8Operands<D, NT>* i8 = nullptr) {
   const int tok0 = blk * kBlockTokens;
   // plain step: every token of the block is visible to every query (tokens <= L) and, with a fused
   // append, none of them is new (tokens < L)
   if (tok0 + kBlockTokens - 1 < L + (fused ? 0 : 1))
-    block_step<D, NT, false, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, false, NewRows{}, nullptr, nullptr, sc);
+    block_step<D, NT, false, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, false, NewRows{}, nullptr, nullptr, i8);
   else
-    block_step<D, NT, true, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, fused, nr, kdst, vdst, sc);
+    block_step<D, NT, true, kI8>(r, qf, st, tok0, n_valid, lim, scale_log2, lane, fused, nr, kdst, vdst, i8);
 }
 
 // fp32 path: the wavefront whose share holds the new rows copies them into the (token-major) cache
@@ -906,6 +930,46 @@ __device__ inline void load_queries(const AttnParams& p, const Unit& u, bool ena
       if (ok) qv = qrow[t * 4 + grp];
       f.q[nt][t] = __builtin_bit_cast(bf16x8, qv);
     }
+  }
+}
+
+// INT8 caches: the queries are quantized like the cache rows (one scale per token and query head, codes
+// rint(x * 127 / amax)) so that QK^T runs on the INT8 matrix cores.  B operand of the 16x16x64
+// instruction: lane (col, grp) holds query row 16 nt + col, head elements 64 ks + 16 grp .. + 15.
+template <int D, int NT>
+struct QFragI8 {
+  u32x4 q[NT][D / 64];
+  float q_scale_log2[NT];  // row scale (amax / 127) * softmax scale * log2(e)
+  int lim[NT];
+};
+
+template <int D, int NT>
+__device__ inline void load_queries_i8(const AttnParams& p, const Unit& u, bool enable, int col, int grp, QFragI8<D, NT>& f) {
+  const int rows = u.nq * p.g;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int rrow = nt * 16 + col;
+    const bool ok = enable && rrow < rows;
+    const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
+    f.lim[nt] = u.L + i;
+    const uint4* qrow = (const uint4*)((const uint16_t*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D);
+    uint4 raw[D / 64][2];
+    float amax = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 64; ++ks)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        raw[ks][h] = ok ? qrow[ks * 8 + grp * 2 + h] : make_uint4(0, 0, 0, 0);
+        amax = fmaxf(amax, amax8(raw[ks][h]));
+      }
+    amax = rows4_max(amax);  // the four lanes of a row hold a quarter of it each
+    const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 64; ++ks) {
+      const uint2 lo = quantize8(raw[ks][0], inv), hi = quantize8(raw[ks][1], inv);
+      f.q[nt][ks] = u32x4{lo.x, lo.y, hi.x, hi.y};
+    }
+    f.q_scale_log2[nt] = amax / 127.0f * p.scale_log2;
   }
 }
 
@@ -996,9 +1060,14 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     const int n = nA + nB;
     BASS_TRACE(2);
 
-    QFrag<D, NT> qc, qB;
-    load_queries<D, NT>(p, uA, true, col, grp, qc);
-    if constexpr (kPair) load_queries<D, NT>(p, uB, hasB, col, grp, qB);
+    typename std::conditional<kI8, QFragI8<D, NT>, QFrag<D, NT>>::type qc, qB;
+    if constexpr (kI8) {
+      load_queries_i8<D, NT>(p, uA, true, col, grp, qc);
+      if constexpr (kPair) load_queries_i8<D, NT>(p, uB, hasB, col, grp, qB);
+    } else {
+      load_queries<D, NT>(p, uA, true, col, grp, qc);
+      if constexpr (kPair) load_queries<D, NT>(p, uB, hasB, col, grp, qB);
+    }
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
     int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
@@ -1084,8 +1153,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         KvRegs<D> t;
         TokenScales sc;
         dequant_block<D>(r, t, sc);
-        block_dispatch<D, NT, true>(t, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, false,
-                                    cur_new, nullptr, nullptr, &sc);  // the codes are patched already: no fused work inside
+        const I8Operands<D, NT> i8{r.k, qc.q, qc.q_scale_log2, &sc};
+        const bf16x8 no_q[NT][D / 32] = {};
+        block_dispatch<D, NT, true>(t, no_q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, false,
+                                    cur_new, nullptr, nullptr, &i8);  // the codes are patched already: no fused work inside
       } else {
         block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
       }

@@ -1,5 +1,6 @@
 """GPU parity of the INT8 KV cache: codes and scales bit for bit against the quantizer oracle, attention
-over the INT8 cache against the fp64 attention oracle run on the represented values code * scale."""
+over the INT8 cache against the fp64 attention oracle run on the represented values code * scale of the
+quantized queries, keys and values."""
 import numpy as np
 import pytest
 
@@ -25,7 +26,8 @@ def reference(w):
     Kf, Vf = wl.bf16_bits_to_f32(w.K), wl.bf16_bits_to_f32(w.V)
     Kq, Ks = quantize_rows(Kf)
     Vq, Vs = quantize_rows(Vf)
-    O, lse = oracle.verify_attention(wl.bf16_bits_to_f32(w.Q), dequantize_rows(Kq, Ks), dequantize_rows(Vq, Vs),
+    Qq, Qs = quantize_rows(wl.bf16_bits_to_f32(w.Q))   # the kernels quantize the query rows the same way
+    O, lse = oracle.verify_attention(dequantize_rows(Qq, Qs), dequantize_rows(Kq, Ks), dequantize_rows(Vq, Vs),
                                      w.ctx_len, w.draft_len, w.scale)
     return (Kq, Ks, Vq, Vs), O, lse
 
