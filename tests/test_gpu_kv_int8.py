@@ -129,6 +129,25 @@ def test_int8_rows_of_zeros_and_extreme_rows(hip):
     check(hip, w)
 
 
+def test_int8_query_rows_of_zeros_and_extreme_query_rows(hip):
+    # the kernel quantizes each query row (token, query head) on the fly: scale 0 for a row of zeros (uniform
+    # attention over the visible tokens), one dominant element, a constant row (every code 127)
+    w = wl.make_attention("i8q", 2, 4, 2, 128, "bf16", [70, 33], [3, 2], 43, kmax=3, Lcap=96)
+    w.Q[0, 1, 2] = 0
+    one = np.zeros(128, np.float32)
+    one[5] = 50.0
+    w.Q[0, 0, 1] = wl.to_bf16_bits(one + 0.01)
+    w.Q[1, 1, 3] = wl.to_bf16_bits(np.full(128, -0.75, np.float32))
+    (_, _, _, _), Or, _ = reference(w)
+    O, lse, status, _ = run(hip, w)
+    assert status == 0 and np.isfinite(O).all()
+    assert np.abs(O - Or).max() <= TOL
+    # the row of zeros: plain mean of the represented V rows it may see
+    Vq, Vs = quantize_rows(wl.bf16_bits_to_f32(w.V))
+    Vhat = dequantize_rows(Vq, Vs).astype(np.float64)
+    np.testing.assert_allclose(O[0, 1, 2], Vhat[0, :70 + 2, 1].mean(axis=0), atol=TOL)
+
+
 def test_int8_cache_is_about_half_the_bytes(hip):
     import paper_2404_15778_amd as bass
     a = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "bf16", 1.0))
