@@ -39,11 +39,14 @@ struct AcceptParams {
   int32_t* status;
 };
 
+// floor(min(w, 1) * 2^44) in two exact steps: the integer part of w * 2^12, and the fraction of it
+// times 2^32 (scalings by powers of two and v_fract are exact; the conversions truncate).
 __device__ inline uint64_t fixed44(float w) {
   if (!(w > 0.f)) return 0;  // negative residuals and NaN carry no weight
-  double x = (double)w;
-  if (x > 1.0) x = 1.0;
-  return (uint64_t)(x * 17592186044416.0);  // 2^44; truncation = floor for x >= 0
+  const float a = fminf(w, 1.0f) * 4096.0f;
+  const uint32_t hi = (uint32_t)a;
+  const uint32_t lo = (uint32_t)(__builtin_amdgcn_fractf(a) * 4294967296.0f);
+  return ((uint64_t)hi << 32) | lo;
 }
 
 __device__ inline uint64_t wave_sum(uint64_t v) {
