@@ -448,19 +448,24 @@ __device__ inline void partial_stores_done() { __builtin_amdgcn_fence(__ATOMIC_R
 // Counts this wavefront's arrival at one or two units (after partial_stores_done).  A job's
 // `last` result is true if this wavefront delivered the unit's last partial: it then owns the
 // reduction over wavefronts w_lo..w_hi.  Both counters are bumped before either result is awaited.
-__device__ inline int32_t* arrival_counter(const AttnParams& p, const Split& sp, CombineJob& j, int& nparts) {
+// The wavefronts that hold a unit's first and last block (integer divisions: callers do this while their
+// first fetches are under way, not on the way out).
+__device__ inline void set_owners(const Split& sp, CombineJob& j) {
   j.w_lo = sp.owner(j.u.begin);
   j.w_hi = sp.owner(j.u.begin + j.u.nblk - 1);
+}
+
+__device__ inline int32_t* arrival_counter(const AttnParams& p, CombineJob& j, int& nparts) {
   nparts = j.w_hi - j.w_lo + 1;
   return p.counters + (size_t)j.u.b * p.Hkv + j.u.kvh;
 }
 
-__device__ inline void arrive(const AttnParams& p, const Split& sp, int lane, CombineJob& ja, bool& last_a, bool has_b, CombineJob& jb,
+__device__ inline void arrive(const AttnParams& p, int lane, CombineJob& ja, bool& last_a, bool has_b, CombineJob& jb,
                               bool& last_b) {
   int na, nb = 1, old_a = 0, old_b = 0;
-  int32_t* ctr_a = arrival_counter(p, sp, ja, na);
+  int32_t* ctr_a = arrival_counter(p, ja, na);
   int32_t* ctr_b = ctr_a;
-  if (has_b) ctr_b = arrival_counter(p, sp, jb, nb);
+  if (has_b) ctr_b = arrival_counter(p, jb, nb);
   if (na > 1 && lane == 0) old_a = __hip_atomic_fetch_add(ctr_a, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (has_b && nb > 1 && lane == 0) old_b = __hip_atomic_fetch_add(ctr_b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   last_a = na == 1 || __builtin_amdgcn_readfirstlane(old_a) == na - 1;
@@ -1070,6 +1075,9 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     }
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
+    CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};  // who else contributes to our units: needed at the very end only
+    set_owners(sp, ja);
+    set_owners(sp, jb);
     int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
 
     // fused append: the units whose new tokens lie in our blocks get their rows staged in LDS
@@ -1205,9 +1213,8 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     }
     partial_stores_done();
     BASS_TRACE(4);
-    CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};
     bool lastA, lastB;
-    arrive(p, sp, lane, ja, lastA, hasB, jb, lastB);
+    arrive(p, lane, ja, lastA, hasB, jb, lastB);
     BASS_TRACE(5);
 #ifdef BASS_EXP_TRACE
     if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
@@ -1518,8 +1525,9 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
     }
     partial_stores_done();
     CombineJob job{u, 0, 0};
+    set_owners(sp, job);
     bool last, unused;
-    arrive(p, sp, lane, job, last, false, job, unused);
+    arrive(p, lane, job, last, false, job, unused);
     if (last) combine_jobs<4, 0>(p, job, true, job, false, lane);
     x += span;
   }
