@@ -71,6 +71,7 @@ static int attention_waves(bool many_rows = false, bool int8 = false) {
 
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
+  unsigned g_magic;  // ceil(2^20 / g) if g <= 64 and rows_max <= 2048 (then r / g == (r * g_magic) >> 20 for every row r), else 0
   int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
   int nshares;  // stretches the block list is cut into: one per wavefront, or one per workgroup (tile kernel)
   int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
@@ -95,6 +96,13 @@ struct AttnParams {
   long long* trace;
 #endif
 };
+
+// Query row r of a kv head is query token r / g, head r % g of the group.  The division by the run-time
+// group size is a multiplication by a constant the host prepared (a generic integer division is some 35
+// instructions, and these sit on the way to the first fetch and on the way out).
+__device__ inline int row_token(const AttnParams& p, int r) {
+  return p.g_magic ? (int)(((unsigned)r * p.g_magic) >> 20) : r / p.g;
+}
 
 // ---------------------------------------------------------------------------------------
 // Flattened schedule, recomputed by every wavefront from the device-side lengths.
@@ -261,7 +269,7 @@ __device__ inline void zero_rows(const AttnParams& p, int b, int kvh, int row_fr
   for (int r0 = row_from; r0 < rows_all; r0 += rpi) {
     const int r = r0 + lane / lpr;
     if (lane < rpi * lpr && r < rows_all) {
-      const int i = r / p.g, hg = r - i * p.g;
+      const int i = row_token(p, r), hg = r - i * p.g;
       const size_t orow = ((size_t)b * p.kmax + i) * p.Hq + kvh * p.g + hg;
       *(float4*)(p.O + orow * D + (lane % lpr) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
       if (p.lse && lane % lpr == 0) p.lse[orow] = 0.f;
@@ -400,7 +408,7 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
   }
   if (c.rok) {
     const float invL = 1.f / L;
-    const int i = r / p.g, hg = r % p.g;
+    const int i = row_token(p, r), hg = r - i * p.g;
     const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
@@ -926,7 +934,7 @@ __device__ inline void load_queries(const AttnParams& p, const Unit& u, bool ena
   for (int nt = 0; nt < NT; ++nt) {
     const int rrow = row0 + nt * 16 + col;  // row0: first query row of this wavefront (tile kernel)
     const bool ok = enable && rrow < rows;
-    const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
+    const int i = ok ? row_token(p, rrow) : 0, hg = ok ? rrow - i * p.g : 0;
     f.lim[nt] = u.L + i;
     const uint4* qrow = (const uint4*)((const uint16_t*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D);
 #pragma unroll
@@ -955,7 +963,7 @@ __device__ inline void load_queries_i8(const AttnParams& p, const Unit& u, bool 
   for (int nt = 0; nt < NT; ++nt) {
     const int rrow = nt * 16 + col;
     const bool ok = enable && rrow < rows;
-    const int i = ok ? rrow / p.g : 0, hg = ok ? rrow % p.g : 0;
+    const int i = ok ? row_token(p, rrow) : 0, hg = ok ? rrow - i * p.g : 0;
     f.lim[nt] = u.L + i;
     const uint4* qrow = (const uint4*)((const uint16_t*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D);
     uint4 raw[D / 64][2];
@@ -1466,7 +1474,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
         for (int r = 0; r < kRowChunk; ++r) {
           pr[r] = 0.f;
           if (r < nr) {
-            const int rrow = r0 + r, i = rrow / p.g, hg = rrow % p.g;
+            const int rrow = r0 + r, i = row_token(p, rrow), hg = rrow - i * p.g;
             const float* qrow = (const float*)p.Q + (((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg) * D;
             float dot = 0.f;
             for (int d = 0; d < D; d += 4) {
@@ -1601,7 +1609,9 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   read_pad_override();
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
-  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max; p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
+  p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max;
+  p.g_magic = (g <= 64 && rows_max <= 2048) ? ((1u << 20) + (unsigned)g - 1u) / (unsigned)g : 0u;  // exact there: checked exhaustively
+  p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
   // bf16 caches, more than one query tile per kv head: the workgroup-level kernel, one stretch per
   // workgroup (default 256, measured best: fewer partials to merge; a wavefront setting W gives W / 2)
   const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16;
