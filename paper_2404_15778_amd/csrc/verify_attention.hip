@@ -49,13 +49,22 @@ static int g_append_pad = 3;      // virtual blocks per unit when the append is 
 static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
 static int g_wpw = 4;             // wavefronts per workgroup
 // Diagnostic build only (-DBASS_EXP_TRACE): every wavefront records wall-clock stamps of its phases
-// (schedule known, streaming done, stores acknowledged, arrival counted, delivered) into a caller's
-// buffer of 16 int64 per wavefront; the product build compiles none of it.
+// (schedule known, first fetch issued, first step done, streaming done, stores acknowledged, arrival
+// counted, delivered) and writes them into a caller's buffer of 16 int64 per wavefront when it is done.
+// The stamps wait in registers until then (low words, 10 ns ticks): a store in the middle of the kernel
+// would sit in the wait counts of the K/V fetches and change what is being measured.  The product build
+// compiles none of it.
 #ifdef BASS_EXP_TRACE
 static long long* g_trace = nullptr;
-#define BASS_TRACE(slot) do { if (p.trace && lane == 0) p.trace[(size_t)w * 16 + (slot)] = wall_clock64(); } while (0)
+#define BASS_TRACE_DECL() unsigned tr_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define BASS_TRACE(slot) do { tr_[slot] = (unsigned)wall_clock64(); } while (0)
+#define BASS_TRACE_VAL(slot, v) do { tr_[slot] = (unsigned)(v); } while (0)
+#define BASS_TRACE_FLUSH() do { if (p.trace && lane == 0) { _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) p.trace[(size_t)w * 16 + i_] = tr_[i_]; } } while (0)
 #else
+#define BASS_TRACE_DECL() do { } while (0)
 #define BASS_TRACE(slot) do { } while (0)
+#define BASS_TRACE_VAL(slot, v) do { } while (0)
+#define BASS_TRACE_FLUSH() do { } while (0)
 #endif
 
 // many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
@@ -1033,9 +1042,11 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   const int lane = threadIdx.x & 63;
   const int w = blockIdx.x * p.wpw + (threadIdx.x >> 6);
   const int col = lane & 15, grp = lane >> 4;
+  BASS_TRACE_DECL();
   BASS_TRACE(0);
 
   const Sched sched = make_sched(p, lane, w == 0);
+  BASS_TRACE(13);
   const int total = sched.total * p.Hkv;
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
@@ -1044,7 +1055,9 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   BASS_TRACE(1);
 
   while (x < x_end) {
+    BASS_TRACE(9);
     const Unit uA = locate(p, sched, x, lane);
+    BASS_TRACE(10);
     const int spanA = min(x_end, uA.begin + uA.nblk + p.pad) - x;  // our stretch of unit A, virtual blocks included
     const int nA = min(spanA, uA.begin + uA.nblk - x);              // real blocks of unit A that are ours
     if (nA <= 0) {  // only virtual blocks of this unit fall into our share
@@ -1059,6 +1072,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     Regs r0;
     if constexpr (kI8) load_block_i8<D>(r0, kc + vecA, vc + vecA, lane, grp);
     else load_block<D>(r0, kc + vecA + lane, vc + vecA + lane);
+    BASS_TRACE(15);
     Unit uB = uA;
     int nB = 0, spanB = 0;
     bool hasB = false;
@@ -1188,6 +1202,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
+        if (s == 0) BASS_TRACE(8);
         fetch(r0, s + 3);
         if (s + 1 < n) step(r1, s + 1);
         fetch(r1, s + 4);
@@ -1208,14 +1223,13 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       }
     }
     BASS_TRACE(3);
-#ifdef BASS_EXP_TRACE
-    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 11] = (hasB ? 1 : 0) + (fused && ((x - uA.begin + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n;
-    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 12] = __builtin_amdgcn_s_getreg(6164);  // XCC_ID
-#endif
+    BASS_TRACE_VAL(11, (hasB ? 1 : 0) + (fused && ((x - uA.begin + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n);
+    BASS_TRACE_VAL(12, __builtin_amdgcn_s_getreg(6164));  // XCC_ID
 
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
     if (!p.fused_reduce) {  // a second launch merges the partials
+      BASS_TRACE_FLUSH();
       x += spanA + spanB;
       continue;
     }
@@ -1224,11 +1238,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     bool lastA, lastB;
     arrive(p, lane, ja, lastA, hasB, jb, lastB);
     BASS_TRACE(5);
-#ifdef BASS_EXP_TRACE
-    if (p.trace && lane == 0) p.trace[(size_t)w * 16 + 7] = (lastA ? 1 : 0) + (lastB ? 2 : 0);
-#endif
+    BASS_TRACE_VAL(7, (lastA ? 1 : 0) + (lastB ? 2 : 0));
     if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane);
     BASS_TRACE(6);
+    BASS_TRACE_FLUSH();
     x += spanA + spanB;
   }
 }
