@@ -335,11 +335,13 @@ __device__ inline float2 load_dev2(__amdgpu_buffer_rsrc_t rs, unsigned byte_off)
   return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
 }
 
-template <int KC, int DC>
+// A sweep merges 64 / LPR rows: LPR lanes share a row, lane dl of them holds the 16-byte chunks dl + LPR k
+// (k < KC) of it.
+template <int KC, int DC, int LPR = 16>
 __device__ inline void combine_issue(const AttnParams& p, const CombineJob& job, int r0, int lane, CombineRegs<KC>& c) {
   const Unit& u = job.u;
   const int D = DC > 0 ? DC : p.D;
-  const int rr = lane >> 4, dl = lane & 15;
+  const int rr = lane / LPR, dl = lane % LPR;
   const int rows = uniform(u.nq * p.g);
   const int S8 = min(uniform(job.w_hi - job.w_lo + 1), 8);
   const size_t slot0 = (size_t)uniform(job.w_lo + u.b * p.Hkv + u.kvh);
@@ -355,18 +357,18 @@ __device__ inline void combine_issue(const AttnParams& p, const CombineJob& job,
     c.ml[j] = load_dev2(rs_ml, (unsigned)j * ml_bytes + ml_off);
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
-      const int d = 4 * (dl + 16 * k);
+      const int d = 4 * (dl + LPR * k);
       const unsigned row_off = (c.rok && d < D) ? (unsigned)(c.r * D + d) * 4 : kNoSuchOffset;
       c.a[j][k] = load_dev4(rs, (unsigned)j * slot_bytes + row_off);
     }
   }
 }
 
-template <int KC, int DC>
+template <int KC, int DC, int LPR = 16>
 __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job, int lane, const CombineRegs<KC>& c) {
   const Unit& u = job.u;
   const int D = DC > 0 ? DC : p.D;
-  const int dl = lane & 15;
+  const int dl = lane % LPR;
   const int S = uniform(job.w_hi - job.w_lo + 1);
   const size_t slot0 = (size_t)uniform(job.w_lo + u.b * p.Hkv + u.kvh);
   const unsigned slot_bytes = (unsigned)p.rows_max * D * 4, ml_bytes = (unsigned)p.rows_max * 8;
@@ -409,7 +411,7 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
       L = fmaf(ml.y, w, L);
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
-        const int d = 4 * (dl + 16 * k);
+        const int d = 4 * (dl + LPR * k);
         const unsigned row_off = (c.rok && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
         acc[k] += load_dev4(rs, (unsigned)j * slot_bytes + row_off) * w;
       }
@@ -421,39 +423,43 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
     const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
-      const int d = 4 * (dl + 16 * k);
+      const int d = 4 * (dl + LPR * k);
       if (d < D) *(f32x4*)(p.O + orow * D + d) = acc[k] * invL;
     }
     if (p.lse && dl == 0) p.lse[orow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
   }
 }
 
-// Reduction of the one or two units this wavefront completed.  The sweeps (4 rows each) of both
-// jobs are laid end to end and handled two at a time, so that two sweeps share one round trip.
-template <int KC, int DC>
+// Reduction of the one or two units this wavefront completed.  The sweeps of both jobs are laid end to
+// end and handled two at a time, so that two sweeps share one round trip.  With a compile-time head size
+// a sweep takes 8 rows (8 lanes per row): a wavefront's merge is bound by its own instruction stream, and
+// the kv heads of this path have at most 16 query rows, mostly 8 or fewer -- one sweep per unit.
+template <int DC>
 __device__ inline void combine_jobs(const AttnParams& p, const CombineJob& ja, bool do_a, const CombineJob& jb, bool do_b,
                                     int lane) {
   constexpr bool kOverlap = DC > 0;  // the run-time-D (fp32) variant has too many chunk registers for two sweeps
+  constexpr int LPR = DC > 0 ? 8 : 16, RPS = 64 / LPR;  // lanes per row, rows per sweep
+  constexpr int KC = DC > 0 ? DC / 4 / LPR : 4;         // 16-byte chunks per lane (fp32: head sizes up to 256)
   const CombineJob& j0 = do_a ? ja : jb;  // first (or only) job
   const bool two = do_a && do_b;
-  const int n0 = (j0.u.nq * p.g + 3) / 4;
-  const int n1 = two ? (jb.u.nq * p.g + 3) / 4 : 0;
+  const int n0 = (j0.u.nq * p.g + RPS - 1) / RPS;
+  const int n1 = two ? (jb.u.nq * p.g + RPS - 1) / RPS : 0;
 #pragma unroll 1
   for (int t = 0; t < n0 + n1; t += (kOverlap ? 2 : 1)) {
     const bool has_y = kOverlap && t + 1 < n0 + n1;
     const CombineJob jx = (t < n0) ? j0 : jb;
-    const int rx = (t < n0) ? 4 * t : 4 * (t - n0);
+    const int rx = (t < n0) ? RPS * t : RPS * (t - n0);
     const CombineJob jy = (t + 1 < n0) ? j0 : jb;
-    const int ry = (t + 1 < n0) ? 4 * (t + 1) : 4 * (t + 1 - n0);
+    const int ry = (t + 1 < n0) ? RPS * (t + 1) : RPS * (t + 1 - n0);
     CombineRegs<KC> cx;
-    combine_issue<KC, DC>(p, jx, rx, lane, cx);
+    combine_issue<KC, DC, LPR>(p, jx, rx, lane, cx);
     if constexpr (kOverlap) {
       CombineRegs<KC> cy;
-      if (has_y) combine_issue<KC, DC>(p, jy, ry, lane, cy);
-      combine_finish<KC, DC>(p, jx, lane, cx);
-      if (has_y) combine_finish<KC, DC>(p, jy, lane, cy);
+      if (has_y) combine_issue<KC, DC, LPR>(p, jy, ry, lane, cy);
+      combine_finish<KC, DC, LPR>(p, jx, lane, cx);
+      if (has_y) combine_finish<KC, DC, LPR>(p, jy, lane, cy);
     } else {
-      combine_finish<KC, DC>(p, jx, lane, cx);
+      combine_finish<KC, DC, LPR>(p, jx, lane, cx);
     }
   }
 }
@@ -1239,7 +1245,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     arrive(p, lane, ja, lastA, hasB, jb, lastB);
     BASS_TRACE(5);
     BASS_TRACE_VAL(7, (lastA ? 1 : 0) + (lastB ? 2 : 0));
-    if (lastA || lastB) combine_jobs<D / 64, D>(p, ja, lastA, jb, lastB, lane);
+    if (lastA || lastB) combine_jobs<D>(p, ja, lastA, jb, lastB, lane);
     BASS_TRACE(6);
     BASS_TRACE_FLUSH();
     x += spanA + spanB;
@@ -1549,7 +1555,7 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
     set_owners(sp, job);
     bool last, unused;
     arrive(p, lane, job, last, false, job, unused);
-    if (last) combine_jobs<4, 0>(p, job, true, job, false, lane);
+    if (last) combine_jobs<0>(p, job, true, job, false, lane);
     x += span;
   }
 }
