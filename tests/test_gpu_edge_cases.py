@@ -66,6 +66,18 @@ def test_more_sequences_than_lanes(hip):
         check(hip, w, fused=(dtype == "bf16"))
 
 
+def test_group_sizes_around_the_multiply_shift_division(hip):
+    # a query row r of a kv head is token r / g, head r % g of the group; the kernels divide by g with a
+    # host-prepared multiply-shift up to g = 64 and with a plain division beyond (fp32 only: the matrix-core
+    # kernels stop at 64 rows per kv head)
+    for Hq, Hkv in ((3, 1), (7, 1), (64, 1), (65, 1), (130, 2), (96, 1)):
+        w = wl.make_attention(f"g{Hq // Hkv}", 2, Hq, Hkv, 64, "fp32", [45, 70], [3, 2], 19, kmax=3, Lcap=80)
+        check(hip, w)
+    for Hq, Hkv in ((3, 1), (6, 2), (7, 1), (63, 1)):
+        w = wl.make_attention(f"g{Hq // Hkv}b", 2, Hq, Hkv, 64, "bf16", [45, 70], [1, 1], 23, kmax=1, Lcap=80)
+        check(hip, w, fused=True)
+
+
 def test_largest_row_count_bf16(hip):
     # kmax * (Hq / Hkv) = 64 query rows per kv head: four 16-row tiles
     w = wl.make_attention("rows64", 2, 16, 2, 128, "bf16", [100, 37], [8, 5], 7, kmax=8, Lcap=128)
