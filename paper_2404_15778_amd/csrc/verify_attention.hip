@@ -502,7 +502,9 @@ __device__ inline void arrive(const AttnParams& p, int lane, CombineJob& ja, boo
 // Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
 // They belong to no wavefront's share of blocks, so wavefront w clears them for the units
 // w, w + nwaves, ... right at the start, off the critical path.
-template <int DC>
+// kInactiveOnly: only the units of sequences without query tokens (they have no blocks, hence no
+// wavefront of their own); the caller then clears the unused rows of the other units elsewhere.
+template <int DC, bool kInactiveOnly = false>
 __device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int nw, int lane) {
   for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
     const int b = unit / p.Hkv;
@@ -514,7 +516,7 @@ __device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int
       bool bad;
       seq_blocks(p, b, L, nq, bad);
     }
-    zero_rows<DC>(p, b, unit - b * p.Hkv, nq * p.g, lane);
+    if (!kInactiveOnly || nq == 0) zero_rows<DC>(p, b, unit - b * p.Hkv, nq * p.g, lane);
   }
 }
 
@@ -1057,7 +1059,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
-  zero_unused_rows<D>(p, sched, w, p.nwaves, lane);
+  // Unused query rows: those of inactive sequences here; those of a unit by the wavefront that holds the
+  // unit's last block, right before its partial stores (that wavefront is handed fewer real blocks, and
+  // the stores are then acknowledged together with the partials instead of holding up the first fetch).
+  zero_unused_rows<D, true>(p, sched, w, p.nwaves, lane);
   BASS_TRACE(1);
 
   while (x < x_end) {
@@ -1232,6 +1237,8 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     BASS_TRACE_VAL(11, (hasB ? 1 : 0) + (fused && ((x - uA.begin + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n);
     BASS_TRACE_VAL(12, __builtin_amdgcn_s_getreg(6164));  // XCC_ID
 
+    if (x - uA.begin + nA == uA.nblk) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
+    if (hasB && nB == uB.nblk) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
     if (!p.fused_reduce) {  // a second launch merges the partials
