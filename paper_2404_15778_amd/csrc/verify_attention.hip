@@ -47,6 +47,8 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 static int g_attention_waves = 0;  // 0 = default
 static int g_append_pad = 3;      // virtual blocks per unit when the append is fused (measured best: 3)
 static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
+static int g_append_before = 1;   // how many of those sit in front of the unit's last real block (one-tile matrix-core
+static int g_plain_before = 0;    // kernel; measured: +0.5 % with the fused append, slightly slower without)
 static int g_wpw = 4;             // wavefronts per workgroup
 // Diagnostic build only (-DBASS_EXP_TRACE): every wavefront records wall-clock stamps of its phases
 // (schedule known, first fetch issued, first step done, streaming done, stores acknowledged, arrival
@@ -83,7 +85,8 @@ struct AttnParams {
   unsigned g_magic;  // ceil(2^20 / g) if g <= 64 and rows_max <= 2048 (then r / g == (r * g_magic) >> 20 for every row r), else 0
   int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
   int nshares;  // stretches the block list is cut into: one per wavefront, or one per workgroup (tile kernel)
-  int pad;  // virtual blocks appended to every unit in the flattened list (see padded_blocks)
+  int pad;  // virtual blocks of every unit in the flattened list (see padded_blocks)
+  int pad_before;  // how many of them sit in front of the unit's last real block instead of behind it (see real_below)
   int span;  // BASS-PAD variant: every active sequence is processed over at least this many cache
              // positions (0: over its own length); the positions beyond its length are masked
   int fused_reduce;  // 1: the last-arriving wavefront merges a unit's partials; 0: a second launch does
@@ -141,6 +144,18 @@ __device__ inline int wave_incl_scan(int v, int lane) {
 // unit's last blocks (with the fused append: copying the step's rows into the cache first), so
 // that this wavefront is handed correspondingly fewer real blocks and finishes with the others.
 __device__ inline int padded_blocks(const AttnParams& p, int nblk) { return nblk > 0 ? nblk + p.pad : 0; }
+
+// Where a unit's virtual blocks sit.  With all of them behind the last real block, the wavefront that holds
+// that block gets between none and all of the credit, depending on where the even cut falls, and the next
+// wavefront the rest.  With pb of them in front of the last real block and the others behind it, it gets
+// at least min(pb, pad - pb): its stretch reaches the last block through the ones in front or leaves it
+// through the ones behind.  A unit's entries are then: real blocks 0 .. nblk-2, pb virtual ones, the last
+// real block, pad - pb virtual ones.  (pb = 0 wherever stretches are not longer than a unit's pad, so that
+// no stretch can lie between two real blocks of a unit without holding one.)
+__device__ inline int real_below(int t, int nblk, int pb) {  // real blocks at entries below t, 0 <= t <= nblk + pad
+  return min(t, nblk - 1) + (t > nblk - 1 + pb ? 1 : 0);
+}
+__device__ inline int entry_of(int j, int nblk, int pb) { return j < nblk - 1 ? j : j + pb; }  // entry of real block j
 
 __device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bool& bad) {
   L = p.ctx_len[b];
@@ -473,9 +488,9 @@ __device__ inline void partial_stores_done() { __builtin_amdgcn_fence(__ATOMIC_R
 // reduction over wavefronts w_lo..w_hi.  Both counters are bumped before either result is awaited.
 // The wavefronts that hold a unit's first and last block (integer divisions: callers do this while their
 // first fetches are under way, not on the way out).
-__device__ inline void set_owners(const Split& sp, CombineJob& j) {
-  j.w_lo = sp.owner(j.u.begin);
-  j.w_hi = sp.owner(j.u.begin + j.u.nblk - 1);
+__device__ inline void set_owners(const Split& sp, CombineJob& j, int pb = 0) {
+  j.w_lo = sp.owner(j.u.begin + entry_of(0, j.u.nblk, pb));
+  j.w_hi = sp.owner(j.u.begin + entry_of(j.u.nblk - 1, j.u.nblk, pb));
 }
 
 __device__ inline int32_t* arrival_counter(const AttnParams& p, CombineJob& j, int& nparts) {
@@ -1059,6 +1074,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   const Split sp = make_split(total, p.nshares);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);
+  const int pb = sp.per > p.pad ? p.pad_before : 0;  // see real_below
   // Unused query rows: those of inactive sequences here; those of a unit by the wavefront that holds the
   // unit's last block, right before its partial stores (that wavefront is handed fewer real blocks, and
   // the stores are then acknowledged together with the partials instead of holding up the first fetch).
@@ -1070,14 +1086,15 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     const Unit uA = locate(p, sched, x, lane);
     BASS_TRACE(10);
     const int spanA = min(x_end, uA.begin + uA.nblk + p.pad) - x;  // our stretch of unit A, virtual blocks included
-    const int nA = min(spanA, uA.begin + uA.nblk - x);              // real blocks of unit A that are ours
+    const int firstA = real_below(x - uA.begin, uA.nblk, pb);         // our first real block of unit A ...
+    const int nA = real_below(x - uA.begin + spanA, uA.nblk, pb) - firstA;  // ... and how many
     if (nA <= 0) {  // only virtual blocks of this unit fall into our share
       x += spanA;
       continue;
     }
     // the share's first block is fetched right away; what follows (the second unit, the queries, the
     // rows of a fused append, ...) runs while that fetch is under way
-    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + (x - uA.begin)) * kBlkVec;
+    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + firstA) * kBlkVec;
     const uint4* kc = (const uint4*)p.Kc;
     const uint4* vc = (const uint4*)p.Vc;
     Regs r0;
@@ -1092,7 +1109,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         hasB = true;
         uB = locate(p, sched, x + spanA, lane);  // starts at its block 0
         spanB = min(x_end, uB.begin + uB.nblk + p.pad) - (x + spanA);
-        nB = min(spanB, uB.nblk);
+        nB = real_below(spanB, uB.nblk, pb);
       }
     }
     const int n = nA + nB;
@@ -1109,9 +1126,9 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
     CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};  // who else contributes to our units: needed at the very end only
-    set_owners(sp, ja);
-    set_owners(sp, jb);
-    int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = x - uA.begin;  // block index = cur_blk + s
+    set_owners(sp, ja, pb);
+    set_owners(sp, jb, pb);
+    int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = firstA;  // block index = cur_blk + s
 
     // fused append: the units whose new tokens lie in our blocks get their rows staged in LDS
     const bool fused = p.Knew != nullptr;
@@ -1124,7 +1141,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     const NewRows newB{newA.k_off + lds_unit, newA.v_off + lds_unit, newA.ks_off + lds_unit, newA.vs_off + lds_unit,
                        uB.L, uB.nq};
     NewRows cur_new = newA;
-    const bool stageA = fused && uA.nq > 0 && (x - uA.begin + nA) * kBlockTokens > uA.L;
+    const bool stageA = fused && uA.nq > 0 && (firstA + nA) * kBlockTokens > uA.L;
     const bool stageB = fused && hasB && uB.nq > 0 && nB * kBlockTokens > uB.L;
     // one set of staging registers: a share that holds the new tokens of both its units is rare (the
     // second unit then lies wholly inside the share) and stages the second unit's rows afterwards
@@ -1234,10 +1251,10 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       }
     }
     BASS_TRACE(3);
-    BASS_TRACE_VAL(11, (hasB ? 1 : 0) + (fused && ((x - uA.begin + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n);
+    BASS_TRACE_VAL(11, (hasB ? 1 : 0) + (fused && ((firstA + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n);
     BASS_TRACE_VAL(12, __builtin_amdgcn_s_getreg(6164));  // XCC_ID
 
-    if (x - uA.begin + nA == uA.nblk) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
+    if (firstA + nA == uA.nblk) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
     if (hasB && nB == uB.nblk) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
@@ -1600,16 +1617,20 @@ extern "C" size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* d)
 
 namespace bass {
 
-// BASS_ATTN_PAD="<fused>,<plain>" overrides the virtual blocks per unit (tuning experiments).
+// BASS_ATTN_PAD="<fused>,<plain>[,<wavefronts per workgroup>[,<in front, fused>,<in front, plain>]]" overrides the
+// virtual blocks per unit and where they sit (tuning experiments).
 static void read_pad_override() {
   static bool done = false;
   if (done) return;
   done = true;
   if (const char* e = getenv("BASS_ATTN_PAD")) {
-    int a = -1, b = -1, c = 4;
-    if (sscanf(e, "%d,%d,%d", &a, &b, &c) >= 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8 && c >= 1 && c <= 4) {
+    int a = -1, b = -1, c = 4, fa = g_append_before, fb = g_plain_before;
+    if (sscanf(e, "%d,%d,%d,%d,%d", &a, &b, &c, &fa, &fb) >= 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8 && c >= 1 && c <= 4 &&
+        fa >= 0 && fb >= 0) {
       g_append_pad = a;
       g_plain_pad = b;
+      g_append_before = fa < a ? fa : a;
+      g_plain_before = fb < b ? fb : b;
       g_wpw = c;
     }
   }
@@ -1643,9 +1664,11 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16;
   p.nshares = !tiles ? p.nwaves : g_attention_waves > 0 ? std::max(16, p.nwaves / 2) : 256;
   p.pad = K_new ? g_append_pad : g_plain_pad;
+  p.pad_before = 0;  // set below for the kernel that supports it
   p.span = span;
   // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
   p.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || rows_max <= 16) ? 1 : 0;
+  if (mfma && rows_max <= 16) p.pad_before = std::min(p.pad, K_new ? g_append_before : g_plain_before);
   p.scale_log2 = d->scale * 1.4426950408889634f;
   p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.Knew = K_new; p.Vnew = V_new;
   p.ctx_len = ctx_len; p.draft_len = draft_len;
