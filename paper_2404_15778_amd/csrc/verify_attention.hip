@@ -515,10 +515,10 @@ __device__ inline void arrive(const AttnParams& p, int lane, CombineJob& ja, boo
 }
 
 // Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
-// They belong to no wavefront's share of blocks, so wavefront w clears them for the units
-// w, w + nwaves, ... right at the start, off the critical path.
+// Wavefront w clears them for the units w, w + nwaves, ... at the start of the kernel.
 // kInactiveOnly: only the units of sequences without query tokens (they have no blocks, hence no
-// wavefront of their own); the caller then clears the unused rows of the other units elsewhere.
+// wavefront of their own); the caller then clears the unused rows of the other units elsewhere (the
+// one-tile matrix-core kernel: by the wavefront that holds the unit's last block).
 template <int DC, bool kInactiveOnly = false>
 __device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int nw, int lane) {
   for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
