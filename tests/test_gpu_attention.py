@@ -203,3 +203,26 @@ def test_grouped_query_shapes_over_work_spreads_and_variants(hip, D, Hq, Hkv, km
             assert np.abs(lse - lser).max() <= TOL["bf16"], variant
     finally:
         bass.bass_set_attention_waves(0)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_lengths_and_work_spreads(hip, seed):
+    # the even split of the block list, the units' virtual blocks (behind and in front of the last real
+    # block) and the contributor ranges of the split-context merge, over random lengths and spreads: short
+    # units, units of one block, stretches shorter and longer than a unit, inactive sequences
+    rng = np.random.default_rng([seed, 0x5C4ED])
+    for _ in range(5):
+        B = int(rng.integers(1, 7))
+        kmax = int(rng.integers(1, 7))
+        ctx = rng.integers(0, 330, size=B)
+        ctx[rng.random(B) < 0.3] = rng.integers(0, 40, size=int((rng.random(B) < 0.3).sum()) or 1)[0]
+        nq = rng.integers(0, kmax + 1, size=B)
+        if nq.max() == 0:
+            nq[0] = 1
+        Hkv = int(rng.choice([1, 2, 4]))
+        D = int(rng.choice([64, 128]))
+        waves = int(rng.choice([64, 68, 128, 192, 320, 512, 768, 1024]))
+        w = wl.make_attention(f"rnd{seed}", B, Hkv, Hkv, D, "bf16", ctx, nq, int(rng.integers(1 << 30)), kmax=kmax,
+                              Lcap=int(ctx.max()) + kmax + int(rng.integers(0, 40)))
+        for fused in (False, True):
+            check_against_oracle(hip, w, waves=waves, fused=fused)
