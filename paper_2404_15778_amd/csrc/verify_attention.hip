@@ -433,7 +433,7 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
     }
   }
   if (c.rok) {
-    const float invL = 1.f / L;
+    const float invL = __builtin_amdgcn_rcpf(L);  // 1 ulp: far inside both tolerances, and a fraction of the instructions of a division
     const int i = row_token(p, r), hg = r - i * p.g;
     const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
 #pragma unroll
