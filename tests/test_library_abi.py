@@ -87,3 +87,19 @@ def test_attention_waves_knob_is_clamped():
     assert bass.bass_set_attention_waves(10**6) == 8192
     assert bass.bass_set_attention_waves(1022) == 1020
     assert bass.bass_set_attention_waves(0) == 768
+
+
+def test_kernel_times_summarize_reads_a_kernel_trace(tmp_path, capsys):
+    """Host logic of the timing utility: groups a rocprofv3 kernel trace by kernel, grid and registers."""
+    import argparse
+    from paper_2404_15778_amd import kernel_times
+    trace = tmp_path / "t_kernel_trace.csv"
+    trace.write_text(
+        "Kernel_Name,Grid_Size_X,VGPR_Count,Start_Timestamp,End_Timestamp\n"
+        '"void bass::verify_attn_bf16<128, 1, false>(bass::AttnParams)",49152,256,1000,33000\n'
+        '"void bass::verify_attn_bf16<128, 1, false>(bass::AttnParams)",49152,256,40000,70000\n'
+        '"void at::native::fill(int)",64,8,0,5\n')
+    kernel_times.summarize(argparse.Namespace(trace=str(trace)))
+    out = capsys.readouterr().out.strip().splitlines()
+    assert len(out) == 1 and "verify_attn_bf16<128, 1, false>" in out[0]
+    assert "n=2" in out[0] and "avg 31.00 us" in out[0] and "min 30.00 us" in out[0]
