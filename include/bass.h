@@ -175,9 +175,9 @@ int bass_verify_attention_split(const bass_attn_desc* desc, const void* Q, const
  * those after the two separate calls (stale rows beyond a sequence's new length may differ); O and
  * lse agree with them up to rounding (the fused launch cuts the context at other points).  Rows of
  * sequences whose lengths had to be clamped are appended at the clamped positions.  Arguments as
- * in those calls.  bf16 caches with kmax * D <= 2048 and fp32 caches append inside the attention
- * launch; longer drafts and INT8 caches (whose rows are quantized by the append kernel) run the
- * append as a launch of its own inside this call.
+ * in those calls.  bf16 and INT8 caches with kmax * D <= 2048 and fp32 caches append inside the
+ * attention launch (INT8: the rows are quantized on the way, with the quantizer of bass_kv_append);
+ * longer drafts run the append as a launch of its own inside this call.
  */
 int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, const void* K_new,
                                  const void* V_new, void* Kcache, void* Vcache,
