@@ -12,19 +12,22 @@
 // values is exact there).  The draw uses integer weights floor(min(w,1) * 2^44), so sums
 // are associative and the wavefront-parallel reduction order cannot change the result.
 //
-// One workgroup of 16 wavefronts per sequence.  Each wavefront sums 256-entry tiles of the
-// chosen row (pair) with 16-byte loads and keeps the tile sums in LDS; the first wavefront
-// then locates the tile and the entry where the cumulative weight first exceeds the
-// threshold, re-reading only that tile.
+// One workgroup of 16 wavefronts per sequence.  Each wavefront sums chunks of 1024 consecutive
+// entries of the chosen row (pair) -- four 16-byte loads per lane and row -- and keeps the chunk
+// sums in LDS; the first wavefront then locates the chunk and the entry where the cumulative
+// weight first exceeds the threshold, re-reading only that chunk.  The pass over the row is bound
+// by the instruction stream of the one compute unit that has the sequence (V entries x instructions
+// per entry), so the weight is five instructions and there is one wave reduction per 1024 entries.
 #include "bass_common.h"
 
 namespace bass {
 
 constexpr int kAcceptThreads = 1024;
 constexpr int kAcceptWaves = kAcceptThreads / kWave;
-constexpr int kTile = 256;                    // entries per wavefront tile: 4 per lane
+constexpr int kTile = 256;                    // entries per wavefront load: 4 per lane
+constexpr int kChunk = 4 * kTile;             // entries per chunk sum: 16 per lane
 constexpr int kMaxVocab = 1 << 19;            // keeps the weight sum below 2^63
-constexpr int kMaxTiles = kMaxVocab / kTile;  // 2048
+constexpr int kMaxChunks = kMaxVocab / kChunk;  // 512
 
 struct AcceptParams {
   int B, kmax, V;
@@ -42,8 +45,8 @@ struct AcceptParams {
 // floor(min(w, 1) * 2^44) in two exact steps: the integer part of w * 2^12, and the fraction of it
 // times 2^32 (scalings by powers of two and v_fract are exact; the conversions truncate).
 __device__ inline uint64_t fixed44(float w) {
-  if (!(w > 0.f)) return 0;  // negative residuals and NaN carry no weight
-  const float a = fminf(w, 1.0f) * 4096.0f;
+  // negative residuals and NaN carry no weight: max(NaN, 0) = 0
+  const float a = fminf(fmaxf(w, 0.f), 1.0f) * 4096.0f;
   const uint32_t hi = (uint32_t)a;
   const uint32_t lo = (uint32_t)(__builtin_amdgcn_fractf(a) * 4294967296.0f);
   return ((uint64_t)hi << 32) | lo;
@@ -87,7 +90,7 @@ __device__ inline void weights4(const float* prow, const float* qrow, int j0, in
 }
 
 __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParams a) {
-  __shared__ uint64_t tile_sum[kMaxTiles];
+  __shared__ uint64_t chunk_sum[kMaxChunks];
   __shared__ int sh_first_reject;
   __shared__ int sh_status;
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -118,31 +121,27 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
 
   const float* prow = pb + (size_t)n * V;
   const float* qrow = (n < k) ? qb + (size_t)n * V : nullptr;
-  const int ntiles = (V + kTile - 1) / kTile;
+  const int nchunks = (V + kChunk - 1) / kChunk;
   const bool vec = (V % 4 == 0) && (((uintptr_t)a.p | (uintptr_t)a.q) % 16 == 0);
 
   uint64_t S = 0;
   int tok = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
-    // four tiles per round: all eight 16-byte loads of a round are in flight before the first sum
-    for (int t0 = wave; t0 < ntiles; t0 += 4 * kAcceptWaves) {
+    // a chunk per wavefront and round: all eight 16-byte loads are in flight before the first sum
+    for (int c = wave; c < nchunks; c += kAcceptWaves) {
       uint64_t w[4][4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = min(t0 + r * kAcceptWaves, ntiles - 1);  // a tile past the end repeats the last one, unused
-        weights4(prow, qrow, t * kTile + 4 * lane, V, vec, w[r]);
-      }
+      for (int r = 0; r < 4; ++r) weights4(prow, qrow, c * kChunk + r * kTile + 4 * lane, V, vec, w[r]);  // entries >= V weigh 0
+      uint64_t mine = 0;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = t0 + r * kAcceptWaves;
-        const uint64_t sum = wave_sum(w[r][0] + w[r][1] + w[r][2] + w[r][3]);
-        if (t < ntiles && lane == 0) tile_sum[t] = sum;
-      }
+      for (int r = 0; r < 4; ++r) mine += w[r][0] + w[r][1] + w[r][2] + w[r][3];
+      const uint64_t sum = wave_sum(mine);
+      if (lane == 0) chunk_sum[c] = sum;
     }
     __syncthreads();
     // every wavefront derives the total the same way (integer sums: order is irrelevant)
     uint64_t part = 0;
-    for (int t = lane; t < ntiles; t += 64) part += tile_sum[t];
+    for (int c = lane; c < nchunks; c += 64) part += chunk_sum[c];
     S = wave_sum(part);
     if (S != 0 || qrow == nullptr) break;
     qrow = nullptr;  // p <= q everywhere in fp32: the residual has no mass, draw from p itself
@@ -160,44 +159,51 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
       const uint64_t U = (uint64_t)((double)ur * 4294967296.0);
       // T = (U * S) >> 32 without a 128-bit product: U < 2^32, S < 2^63
       uint64_t T = U * (S >> 32) + ((U * (S & 0xFFFFFFFFull)) >> 32);
-      // tile holding the first cumulative weight > T: lanes own contiguous runs of tiles
-      const int per = (ntiles + 63) / 64;
-      const int t_lo = lane * per, t_hi = min(ntiles, t_lo + per);
+      // chunk holding the first cumulative weight > T: lanes own contiguous runs of chunks
+      const int per = (nchunks + 63) / 64;
+      const int t_lo = lane * per, t_hi = min(nchunks, t_lo + per);
       uint64_t run = 0;
-      for (int t = t_lo; t < t_hi; ++t) run += tile_sum[t];
+      for (int t = t_lo; t < t_hi; ++t) run += chunk_sum[t];
       const uint64_t incl = wave_incl_scan64(run, lane);
       const uint64_t excl = incl - run;
       const unsigned long long hit = __ballot(incl > T);
       const int src = __ffsll((long long)hit) - 1;  // S > T guarantees a hit
-      int tile = 0;
+      int chunk = 0;
       uint64_t before = 0;
       if (lane == src) {
         uint64_t c = excl;
-        tile = t_lo;
+        chunk = t_lo;
         for (int t = t_lo; t < t_hi; ++t) {
-          if (c + tile_sum[t] > T) { tile = t; break; }
-          c += tile_sum[t];
+          if (c + chunk_sum[t] > T) { chunk = t; break; }
+          c += chunk_sum[t];
         }
         before = c;
       }
-      tile = __shfl(tile, src);
+      chunk = __shfl(chunk, src);
       before = (uint64_t)__shfl((unsigned long long)before, src);
-      // inside the tile
-      uint64_t w[4];
-      weights4(prow, qrow, tile * kTile + 4 * lane, V, vec, w);
-      const uint64_t mine = w[0] + w[1] + w[2] + w[3];
+      // inside the chunk: lane l takes its 16 consecutive entries
+      uint64_t w[4][4];
+      uint64_t mine = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        weights4(prow, qrow, chunk * kChunk + 16 * lane + 4 * r, V, vec, w[r]);
+        mine += w[r][0] + w[r][1] + w[r][2] + w[r][3];
+      }
       const uint64_t incl2 = before + wave_incl_scan64(mine, lane);
       const unsigned long long hit2 = __ballot(incl2 > T);
       const int src2 = __ffsll((long long)hit2) - 1;
       if (lane == src2) {
         uint64_t c = incl2 - mine;
         int e = 0;
+        bool found = false;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (c + w[j] > T) { e = j; break; }
-          c += w[j];
+        for (int j = 0; j < 16; ++j) {
+          if (!found) {
+            if (c + w[j >> 2][j & 3] > T) { e = j; found = true; }
+            else c += w[j >> 2][j & 3];
+          }
         }
-        tok = tile * kTile + 4 * lane + e;
+        tok = chunk * kChunk + 16 * lane + e;
       }
       tok = __shfl(tok, src2);
     }
