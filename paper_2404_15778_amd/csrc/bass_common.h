@@ -93,6 +93,42 @@ __device__ inline float amax8(const uint4& v) {
 }
 #endif
 
+// 64-bit inclusive prefix sum and total over a wavefront.  Shifts inside rows of 16 lanes are DPP moves of
+// the two halves (a generic shuffle of a 64-bit value is two trips through the LDS crossbar per step); the
+// three row totals are then added from scalar registers.  Integer sums: the order is irrelevant.
+#ifdef __HIPCC__
+template <int N>
+__device__ inline uint64_t row_shift_right_u64(uint64_t v) {  // lane i of a row gets lane i - N of the row, 0 for i < N
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, 0x110 + N, 0xF, 0xF, true);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), 0x110 + N, 0xF, 0xF, true);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ inline uint64_t read_lane_u64(uint64_t v, int src) {  // src: wave-uniform
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, src);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), src);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ inline uint64_t wave_incl_scan_u64(uint64_t v, int lane) {
+  v += row_shift_right_u64<1>(v);
+  v += row_shift_right_u64<2>(v);
+  v += row_shift_right_u64<4>(v);
+  v += row_shift_right_u64<8>(v);
+  const uint64_t t0 = read_lane_u64(v, 15), t1 = read_lane_u64(v, 31), t2 = read_lane_u64(v, 47);
+  const int row = lane >> 4;
+  return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
+}
+
+__device__ inline uint64_t wave_sum_u64(uint64_t v) {  // the same total in every lane
+  v += row_shift_right_u64<1>(v);
+  v += row_shift_right_u64<2>(v);
+  v += row_shift_right_u64<4>(v);
+  v += row_shift_right_u64<8>(v);
+  return read_lane_u64(v, 15) + read_lane_u64(v, 31) + read_lane_u64(v, 47) + read_lane_u64(v, 63);
+}
+#endif
+
 // Per-sequence lengths with the clamping the header promises.  L = cached tokens before the
 // step, nq = query tokens; on return 0 <= nq <= kmax, 0 <= L, L + nq <= Lcap.
 __device__ inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {

@@ -74,21 +74,6 @@ __device__ inline KeyRange keys_with_prefix(uint32_t prefix, int shift) {
 }
 __device__ inline uint64_t warp_mass(float e) { return has_mass(e) ? mass_of(e) : 0; }
 
-__device__ inline uint64_t wave_sum64(uint64_t v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, o);
-  return v;
-}
-
-__device__ inline uint64_t wave_incl_scan_u64(uint64_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint64_t o = (uint64_t)__shfl_up((unsigned long long)v, d);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
-
 constexpr int kWarpUnroll = 8;  // groups a thread keeps in flight
 
 // W logits per thread and load: 4 (16-byte loads; V a multiple of 4 and 16-byte aligned rows) or 1
@@ -213,7 +198,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
           }
           keep_group(g, k, ev);
         });
-        mine = wave_sum64(mine);
+        mine = wave_sum_u64(mine);
         if (lane == 0) red64[wave] = mine;
         __syncthreads();
         for (int k = 0; k < kWarpWaves; ++k) S += red64[k];

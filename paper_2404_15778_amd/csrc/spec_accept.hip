@@ -52,21 +52,6 @@ __device__ inline uint64_t fixed44(float w) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-__device__ inline uint64_t wave_sum(uint64_t v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += (uint64_t)__shfl_xor((unsigned long long)v, o);
-  return v;
-}
-
-__device__ inline uint64_t wave_incl_scan64(uint64_t v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint64_t o = (uint64_t)__shfl_up((unsigned long long)v, d);
-    if (lane >= d) v += o;
-  }
-  return v;
-}
-
 // The four weights of entries j0..j0+3 (entries >= V weigh 0).  qrow == nullptr: weights are p.
 __device__ inline void weights4(const float* prow, const float* qrow, int j0, int V, bool vec, uint64_t (&w)[4]) {
   float pv[4] = {0.f, 0.f, 0.f, 0.f}, qv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -135,14 +120,14 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
       uint64_t mine = 0;
 #pragma unroll
       for (int r = 0; r < 4; ++r) mine += w[r][0] + w[r][1] + w[r][2] + w[r][3];
-      const uint64_t sum = wave_sum(mine);
+      const uint64_t sum = wave_sum_u64(mine);
       if (lane == 0) chunk_sum[c] = sum;
     }
     __syncthreads();
     // every wavefront derives the total the same way (integer sums: order is irrelevant)
     uint64_t part = 0;
     for (int c = lane; c < nchunks; c += 64) part += chunk_sum[c];
-    S = wave_sum(part);
+    S = wave_sum_u64(part);
     if (S != 0 || qrow == nullptr) break;
     qrow = nullptr;  // p <= q everywhere in fp32: the residual has no mass, draw from p itself
     __syncthreads();
@@ -164,7 +149,7 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
       const int t_lo = lane * per, t_hi = min(nchunks, t_lo + per);
       uint64_t run = 0;
       for (int t = t_lo; t < t_hi; ++t) run += chunk_sum[t];
-      const uint64_t incl = wave_incl_scan64(run, lane);
+      const uint64_t incl = wave_incl_scan_u64(run, lane);
       const uint64_t excl = incl - run;
       const unsigned long long hit = __ballot(incl > T);
       const int src = __ffsll((long long)hit) - 1;  // S > T guarantees a hit
@@ -189,7 +174,7 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
         weights4(prow, qrow, chunk * kChunk + 16 * lane + 4 * r, V, vec, w[r]);
         mine += w[r][0] + w[r][1] + w[r][2] + w[r][3];
       }
-      const uint64_t incl2 = before + wave_incl_scan64(mine, lane);
+      const uint64_t incl2 = before + wave_incl_scan_u64(mine, lane);
       const unsigned long long hit2 = __ballot(incl2 > T);
       const int src2 = __ffsll((long long)hit2) - 1;
       if (lane == src2) {
