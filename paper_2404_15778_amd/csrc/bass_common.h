@@ -120,6 +120,23 @@ __device__ inline uint64_t wave_incl_scan_u64(uint64_t v, int lane) {
   return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
 }
 
+template <int N>
+__device__ inline float row_shift_right_keep(float v) {  // lane i of a row gets lane i - N of the row, its own value for i < N
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x110 + N, 0xF, 0xF, false));
+}
+
+__device__ inline float wave_max_f32(float v) {  // the same maximum in every lane
+  v = fmaxf(v, row_shift_right_keep<1>(v));
+  v = fmaxf(v, row_shift_right_keep<2>(v));
+  v = fmaxf(v, row_shift_right_keep<4>(v));
+  v = fmaxf(v, row_shift_right_keep<8>(v));
+  const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+  const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31));
+  const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47));
+  const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
+}
+
 __device__ inline uint64_t wave_sum_u64(uint64_t v) {  // the same total in every lane
   v += row_shift_right_u64<1>(v);
   v += row_shift_right_u64<2>(v);

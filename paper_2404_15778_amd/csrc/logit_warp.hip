@@ -160,8 +160,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_probs_kernel(WarpParams a) 
 #pragma unroll
     for (int e = 0; e < W; ++e) m = fmaxf(m, gr.v[e]);
   });
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  m = wave_max_f32(m);
   if (lane == 0) redf[wave] = m;
   __syncthreads();
   float zmax = redf[0];

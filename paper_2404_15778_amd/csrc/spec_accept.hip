@@ -164,8 +164,8 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
         }
         before = c;
       }
-      chunk = __shfl(chunk, src);
-      before = (uint64_t)__shfl((unsigned long long)before, src);
+      chunk = __builtin_amdgcn_readlane(chunk, src);  // src is wave-uniform
+      before = read_lane_u64(before, src);
       // inside the chunk: lane l takes its 16 consecutive entries
       uint64_t w[4][4];
       uint64_t mine = 0;
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(kAcceptThreads) void spec_accept_kernel(AcceptParam
         }
         tok = chunk * kChunk + 16 * lane + e;
       }
-      tok = __shfl(tok, src2);
+      tok = __builtin_amdgcn_readlane(tok, src2);
     }
     if (lane == 0) {
       a.n_accept[b] = n;
