@@ -379,6 +379,8 @@ __device__ inline void combine_issue(const AttnParams& p, const CombineJob& job,
   }
 }
 
+constexpr int kMore = 2;  // partials beyond the eighth are fetched this many at a time (registers: the streaming kernel is full)
+
 template <int KC, int DC, int LPR = 16>
 __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job, int lane, const CombineRegs<KC>& c) {
   const Unit& u = job.u;
@@ -397,10 +399,16 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
   for (int j = 0; j < 8; ++j)
     if (j < S) M = fmaxf(M, c.ml[j].x);  // wave-uniform guards: partials beyond S were never requested
   const unsigned row8 = c.rok ? (unsigned)r * 8 : kNoSuchOffset;
-  if (S > 8) {
+  if (S > 8) {  // further partials, eight per round trip (a load per iteration would be a round trip each)
     const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
 #pragma unroll 1
-    for (int j = 8; j < S; ++j) M = fmaxf(M, load_dev2(rs_ml, (unsigned)j * ml_bytes + row8).x);
+    for (int j0 = 8; j0 < S; j0 += 8) {
+      float2 t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = load_dev2(rs_ml, j0 + i < S ? (unsigned)(j0 + i) * ml_bytes + row8 : kNoSuchOffset);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) M = fmaxf(M, j0 + i < S ? t[i].x : -INFINITY);
+    }
   }
   const float Mf = (M == -INFINITY) ? 0.f : M;  // idle row slots only
   float L = 0.f;
@@ -416,19 +424,32 @@ __device__ inline void combine_finish(const AttnParams& p, const CombineJob& job
       for (int k = 0; k < KC; ++k) acc[k] += c.a[j][k] * wgt;
     }
   }
-  if (S > 8) {  // further partials, one at a time
+  if (S > 8) {  // further partials, kMore per round trip: all loads of a round are issued before the first use
     const __amdgpu_buffer_rsrc_t rs = dev_buffer(p.part_acc + slot0 * p.rows_max * D, (unsigned)S * slot_bytes);
     const __amdgpu_buffer_rsrc_t rs_ml = dev_buffer(p.part_ml + slot0 * p.rows_max * 2, (unsigned)S * ml_bytes);
-#pragma unroll 1
-    for (int j = 8; j < S; ++j) {
-      const float2 ml = load_dev2(rs_ml, (unsigned)j * ml_bytes + row8);
-      const float w = __builtin_amdgcn_exp2f(ml.x - Mf);
-      L = fmaf(ml.y, w, L);
+    unsigned row_off[KC];
 #pragma unroll
-      for (int k = 0; k < KC; ++k) {
-        const int d = 4 * (dl + LPR * k);
-        const unsigned row_off = (c.rok && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
-        acc[k] += load_dev4(rs, (unsigned)j * slot_bytes + row_off) * w;
+    for (int k = 0; k < KC; ++k) {
+      const int d = 4 * (dl + LPR * k);
+      row_off[k] = (c.rok && d < D) ? (unsigned)(r * D + d) * 4 : kNoSuchOffset;
+    }
+#pragma unroll 1
+    for (int j0 = 8; j0 < S; j0 += kMore) {
+      float2 ml[kMore];
+      f32x4 a[kMore][KC];
+#pragma unroll
+      for (int i = 0; i < kMore; ++i) {
+        const bool have = j0 + i < S;  // wave-uniform; a missing partial is requested out of range (zeros, no memory access)
+        ml[i] = load_dev2(rs_ml, have ? (unsigned)(j0 + i) * ml_bytes + row8 : kNoSuchOffset);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) a[i][k] = load_dev4(rs, have ? (unsigned)(j0 + i) * slot_bytes + row_off[k] : kNoSuchOffset);
+      }
+#pragma unroll
+      for (int i = 0; i < kMore; ++i) {
+        const float w = j0 + i < S ? __builtin_amdgcn_exp2f(ml[i].x - Mf) : 0.f;
+        L = fmaf(ml[i].y, w, L);
+#pragma unroll
+        for (int k = 0; k < KC; ++k) acc[k] += a[i][k] * w;
       }
     }
   }
