@@ -226,3 +226,13 @@ def test_random_lengths_and_work_spreads(hip, seed):
                               Lcap=int(ctx.max()) + kmax + int(rng.integers(0, 40)))
         for fused in (False, True):
             check_against_oracle(hip, w, waves=waves, fused=fused)
+
+
+@pytest.mark.parametrize("ctx", [1500, 1531, 290])
+@pytest.mark.parametrize("fused", [False, True])
+def test_one_unit_merged_from_dozens_of_partials(hip, ctx, fused):
+    # a single sequence with one kv head spread over more wavefronts than it has blocks: every wavefront
+    # delivers a partial of one block, and the merge goes through its rounds for the partials beyond the
+    # eighth with full and with ragged last rounds (48, 49 and 10 contributors)
+    w = wl.make_attention("one_unit", 1, 1, 1, 128, "bf16", [ctx], [3], ctx, kmax=3, Lcap=ctx + 40)
+    check_against_oracle(hip, w, waves=256, fused=fused)
