@@ -194,3 +194,14 @@ def test_long_appends_at_unaligned_offsets_keep_their_neighbours(hip, dtype, D):
     Kg, _ = da.gather(hip.i32([Lcap - 10, 0, 0]), hip.i32([10, 0, 0]), 10)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(hip.to_host(Kg)[0, :10], Bk[0, :10])
+
+
+@pytest.mark.parametrize("dtype,D,Lcap", [("bf16", 128, 70000), ("fp32", 64, 70000)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_caches_beyond_four_gib(hip, dtype, D, Lcap, fused):
+    # 10 sequences x 32 kv heads x 70 000 tokens of capacity: 5.7 GB per cache tensor, so that the last
+    # sequences' rows lie beyond byte offset 2^32 (append, fetch and the fused append's stores all address
+    # the cache with 64-bit offsets); the contexts themselves are short, so the oracle covers every row
+    w = wl.make_attention("big_cache", 10, 32, 32, D, dtype, [300, 0, 17, 64, 1, 100, 33, 250, 5, 129],
+                          [4, 1, 2, 3, 4, 1, 2, 3, 4, 1], 7, kmax=4, Lcap=Lcap)
+    check(hip, w, fused)

@@ -153,3 +153,11 @@ def test_int8_cache_is_about_half_the_bytes(hip):
     a = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "bf16", 1.0))
     b = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "int8kv", 1.0))
     assert abs(b / a - (128 + 4) / 256) < 1e-9   # D + 4 bytes per token and head instead of 2 D
+
+
+@pytest.mark.parametrize("two_step", [True, False])
+def test_int8_cache_beyond_four_gib(hip, two_step):
+    # 10 x 32 heads x 140 000 tokens of capacity: 5.9 GB per INT8 cache tensor; short contexts, every row checked
+    w = wl.make_attention("i8big", 10, 32, 32, 128, "bf16", [300, 0, 17, 64, 1, 100, 33, 250, 5, 129],
+                          [4, 1, 2, 3, 4, 1, 2, 3, 4, 1], 9, kmax=4, Lcap=140000)
+    check(hip, w, two_step=two_step)
