@@ -61,3 +61,21 @@ def test_full_size_sampled_rows(hip, make, nsample):
     np.testing.assert_array_equal(O2, O3)
     np.testing.assert_array_equal(lse2, lse3)
     assert np.abs(O2 - O).max() <= 5e-3 and np.abs(lse2 - lse).max() <= 5e-3
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (16, 2)])
+def test_one_very_long_context(hip, Hq, Hkv):
+    # 100 000 cached tokens in one sequence next to a short one (3 126 blocks per kv head, spread over the
+    # whole chip; dozens of partials per unit); one query tile per kv head and three (grouped queries)
+    w = wl.make_attention("long_ctx", 2, Hq, Hkv, 128, "bf16", [100000, 40], [3, 2], 11, kmax=3, Lcap=100008)
+    O, lse, status, _ = hip.run_attention_workload(w, poison=True, fused=True)
+    assert status == 0 and np.isfinite(O).all() and np.isfinite(lse).all()
+    worst = 0.0
+    for b in range(w.B):
+        for i in range(int(w.draft_len[b])):
+            for h in sorted({0, Hq // 2, Hq - 1}):
+                ref, lref = oracle.verify_attention_row(w.Q, w.K, w.V, b, i, h, int(w.ctx_len[b]), w.scale)
+                worst = max(worst, float(np.abs(O[b, i, h] - ref).max()))
+                assert abs(float(lse[b, i, h]) - lref) <= TOL, (b, i, h)
+    print(f"long context: worst max-abs error {worst:.3e}", flush=True)
+    assert worst <= TOL
