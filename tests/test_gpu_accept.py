@@ -59,3 +59,11 @@ def test_degenerate_rows_and_status_bits(hip):
     a.n_draft = np.array([2, 2, 2, 5], np.int32)  # 5 > kmax -> clamped
     got = check(hip, a)
     assert got[2] & 7 == 7
+
+
+@pytest.mark.parametrize("V", [(1 << 19) - 1, 1 << 19])
+def test_largest_vocabulary(hip, V):
+    # 2^19 entries is the limit of the interface (it keeps the integer weight sum below 2^63): 512 chunks of
+    # 1024 entries in the kernel, the last one ragged for 2^19 - 1
+    a = wl.make_accept("vmax", 3, 2, V, 5, 3.0, 1.0, n_draft=[2, 0, 1])
+    check(hip, a)

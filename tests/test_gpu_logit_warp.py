@@ -135,3 +135,14 @@ def test_warped_rows_feed_the_acceptance(hip):
     n_acc, nxt, status = hip.run_accept_workload(a)
     n_ref, t_ref, s_ref = oracle.spec_accept(a.p, a.q, a.draft_tok, a.n_draft, a.u)[:3]
     assert (n_acc == n_ref).all() and (nxt == t_ref).all() and status == s_ref
+
+
+@pytest.mark.parametrize("V", [(1 << 19) - 1, 1 << 19])
+def test_largest_vocabulary(hip, V):
+    # the limit of the interface: rows of 2^19 logits stream through the output row (no register variant)
+    rng = np.random.default_rng(V)
+    logits = (rng.standard_normal((2, V)) * 3).astype(np.float32)
+    for T, top_p in ((0.2, 0.95), (1.0, 0.9)):
+        got, status = hip.run_warp_probs(logits, T, top_p)
+        assert status == 0
+        assert check_rows(logits, T, top_p, got) <= 1
