@@ -67,3 +67,11 @@ def test_largest_vocabulary(hip, V):
     # 1024 entries in the kernel, the last one ragged for 2^19 - 1
     a = wl.make_accept("vmax", 3, 2, V, 5, 3.0, 1.0, n_draft=[2, 0, 1])
     check(hip, a)
+
+
+def test_no_drafts_at_all_is_plain_sampling(hip):
+    # kmax = 0: no draft model rows exist (q and draft_tok are empty); every sequence draws its token from p_0
+    for V in (300, 50000):
+        a = wl.make_accept("k0", 5, 0, V, 3, 2.0, 1.0)
+        n_acc, nxt, st = check(hip, a)
+        assert st == 0 and (n_acc == 0).all()
