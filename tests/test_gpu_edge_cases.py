@@ -55,15 +55,21 @@ def test_cache_filled_to_capacity(hip):
         check(hip, w, fused=True)
 
 
-def test_more_sequences_than_lanes(hip):
-    # 70 sequences: the schedule's 64-sequence register chunk is not enough
-    rng = np.random.default_rng(5)
-    ctx = rng.integers(0, 80, size=70)
-    nq = rng.integers(0, 4, size=70)
-    nq[[0, 64, 69]] = [2, 3, 1]
-    for dtype in ("bf16", "fp32"):
-        w = wl.make_attention("b70", 70, 2, 2, 64, dtype, ctx, nq, 6, kmax=3, Lcap=96)
-        check(hip, w, fused=(dtype == "bf16"))
+@pytest.mark.parametrize("B", [70, 64, 65, 200])
+def test_more_sequences_than_lanes(hip, B):
+    # the schedule keeps 64 sequences at a time in a wavefront's lanes: exactly one chunk, one more sequence,
+    # two chunks, and four with a ragged last one
+    rng = np.random.default_rng(5 if B == 70 else B)
+    ctx = rng.integers(0, 80, size=B)
+    nq = rng.integers(0, 4, size=B)
+    nq[[0, 63, B - 1]] = [2, 3, 1]
+    for dtype in ("bf16", "fp32", "int8"):
+        w = wl.make_attention(f"b{B}", B, 2, 2, 64, "bf16" if dtype == "int8" else dtype, ctx, nq, 6, kmax=3, Lcap=96)
+        if dtype == "int8":
+            import test_gpu_kv_int8 as i8
+            i8.check(hip, w, two_step=False)
+        else:
+            check(hip, w, fused=(dtype == "bf16"))
 
 
 def test_group_sizes_around_the_multiply_shift_division(hip):
