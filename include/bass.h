@@ -40,7 +40,9 @@ enum {
 enum {
   BASS_STATUS_LEN_CLAMPED = 1,      /* a ctx_len / draft_len / n_new / n_draft was out of range */
   BASS_STATUS_TOKEN_CLAMPED = 2,    /* a draft token id was outside [0, V)                      */
-  BASS_STATUS_ZERO_MASS = 4         /* a probability row had no mass to sample from             */
+  BASS_STATUS_ZERO_MASS = 4,        /* a probability row had no mass to sample from             */
+  BASS_STATUS_PLAN_MISMATCH = 8     /* the plan handed to an attention launch was made for another
+                                       shape, work spread or kind of launch; nothing was computed */
 };
 
 /* BASS_DTYPE_INT8KV: Q, K_new, V_new are bf16; the caches hold INT8 codes with one fp32 scale per
@@ -186,6 +188,45 @@ int bass_append_verify_attention(const bass_attn_desc* desc, const void* Q, cons
                                  int32_t* dev_status, void* stream);
 
 /*
+ * A verification step runs the same ragged attention once per layer of the main model, and all layers
+ * see the same lengths (Section 3.2: a sequence's length changes between steps, when its accepted
+ * drafts are known, not inside one).  The division of the ragged work over the GPU is therefore made
+ * once per step -- bass_attention_plan, one small launch -- and every layer's call takes the plan:
+ * bass_verify_attention_planned starts streaming the caches a microsecond earlier than
+ * bass_verify_attention / bass_append_verify_attention, which make a plan of their own inside the call.
+ *
+ * bass_attention_plan_bytes: size of a plan buffer for this shape (0 for a bad shape).
+ * bass_attention_plan: writes the plan for ctx_len / draft_len [B] (device, read when the launch runs)
+ *   into `plan` (device, 16-byte aligned, at least bass_attention_plan_bytes(desc) bytes; no need to clear
+ *   it).  flags: BASS_PLAN_APPEND if the attention calls will bring K_new / V_new (the step's rows are then
+ *   appended as in bass_append_verify_attention), 0 if they will not.  padded_len: as in
+ *   bass_verify_attention_pad (0 = none; not together with BASS_PLAN_APPEND).  Lengths outside the cache
+ *   are clamped as everywhere (BASS_STATUS_LEN_CLAMPED); the plan holds the clamped values.
+ * bass_attention_plan_host: the same plan, byte for byte in every part a launch reads, computed on the
+ *   HOST from HOST arrays into HOST memory (for callers that keep the lengths on the host and copy the
+ *   plan up themselves, and for checking the planner without a GPU); host_status (optional) receives
+ *   BASS_STATUS_LEN_CLAMPED.
+ * bass_verify_attention_planned: the attention of one layer with the step's plan; arguments and results
+ *   as in bass_verify_attention (K_new = V_new = NULL) or bass_append_verify_attention (both given), the
+ *   lengths being those the plan was made from.  The plan must come from bass_attention_plan with the
+ *   same descriptor, the matching flags and the same bass_set_attention_waves setting; a launch that
+ *   finds anything else in `plan` computes nothing and raises BASS_STATUS_PLAN_MISMATCH.  A plan may be
+ *   used by any number of calls; it is read only.
+ */
+enum { BASS_PLAN_APPEND = 1 };
+size_t bass_attention_plan_bytes(const bass_attn_desc* desc);
+int bass_attention_plan(const bass_attn_desc* desc, const int32_t* ctx_len, const int32_t* draft_len,
+                        int32_t flags, int32_t padded_len, void* plan, size_t plan_bytes,
+                        int32_t* dev_status, void* stream);
+int bass_attention_plan_host(const bass_attn_desc* desc, const int32_t* ctx_len_host,
+                             const int32_t* draft_len_host, int32_t flags, int32_t padded_len,
+                             void* plan_host, size_t plan_bytes, int32_t* host_status);
+int bass_verify_attention_planned(const bass_attn_desc* desc, const void* Q, const void* K_new,
+                                  const void* V_new, void* Kcache, void* Vcache, const void* plan,
+                                  float* O, float* lse, void* workspace, size_t workspace_bytes,
+                                  int32_t* dev_status, void* stream);
+
+/*
  * Speculative-sampling acceptance for the batch (Section 2.2: the number of accepted
  * drafts is decided from the main- and draft-model probabilities; on rejection a corrected
  * token is sampled from the main model's outputs; the procedure is equivalent to sampling
@@ -261,6 +302,18 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
  * the first of these cases.
  */
 int bass_set_attention_waves(int waves);
+
+/*
+ * Measurement aid (not part of the verification step): a plain streaming read of the first
+ * floor(bytes_each / 8192) * 8192 bytes of K and of V with the access pattern of the attention kernel
+ * (`waves` wavefronts, each a contiguous share of 8 KiB K blocks and 8 KiB V blocks, 1 KiB per
+ * wavefront load instruction, non-temporal, two blocks in flight) and no arithmetic: the time the memory
+ * system needs for the bytes of an attention launch, which is what Section 3.2 says the step is bound by.
+ * K, V: device, 16-byte aligned; waves: a multiple of 4 in [4, 8192]; sink: device, >= waves words, or
+ * NULL.  Returns the bytes read per launch (K and V together), or a negative BASS_ERR_* code.
+ */
+int64_t bass_bench_stream_read(const void* K, const void* V, size_t bytes_each, int32_t waves,
+                               uint32_t* sink, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libbass.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP = -1, -2, -3, -4
-STATUS_LEN_CLAMPED, STATUS_TOKEN_CLAMPED, STATUS_ZERO_MASS = 1, 2, 4
+STATUS_LEN_CLAMPED, STATUS_TOKEN_CLAMPED, STATUS_ZERO_MASS, STATUS_PLAN_MISMATCH = 1, 2, 4, 8
+PLAN_APPEND = 1
 DTYPE_BF16, DTYPE_FP32, DTYPE_INT8KV = 0, 1, 2
 
 # every symbol include/bass.h declares
@@ -25,6 +26,8 @@ EXPORTS = (
     "bass_kv_append", "bass_kv_gather", "bass_kv_gather_int8", "bass_verify_attention", "bass_verify_attention_pad",
     "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept", "bass_warp_probs",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
+    "bass_attention_plan_bytes", "bass_attention_plan", "bass_attention_plan_host", "bass_verify_attention_planned",
+    "bass_bench_stream_read",
 )
 
 
@@ -94,6 +97,16 @@ def lib():
         L.bass_next_draft_len.argtypes = [ctypes.POINTER(DraftLenState), ctypes.POINTER(i32), i32, i32, i32, i32]
         L.bass_set_attention_waves.restype = ctypes.c_int
         L.bass_set_attention_waves.argtypes = [ctypes.c_int]
+        L.bass_attention_plan_bytes.restype = sz
+        L.bass_attention_plan_bytes.argtypes = [dp]
+        L.bass_attention_plan.restype = ctypes.c_int
+        L.bass_attention_plan.argtypes = [dp, vp, vp, i32, i32, vp, sz, vp, vp]
+        L.bass_attention_plan_host.restype = ctypes.c_int
+        L.bass_attention_plan_host.argtypes = [dp, vp, vp, i32, i32, vp, sz, vp]
+        L.bass_bench_stream_read.restype = ctypes.c_int64
+        L.bass_bench_stream_read.argtypes = [vp, vp, sz, i32, vp, vp]
+        L.bass_verify_attention_planned.restype = ctypes.c_int
+        L.bass_verify_attention_planned.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         _lib = L
     return _lib
 
@@ -284,6 +297,76 @@ def bass_append_verify_attention(desc, Q, K_new, V_new, Kcache, Vcache, ctx_len,
         _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
         ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
         _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_append_verify_attention")
+
+
+def bass_attention_plan_bytes(desc: AttnDesc) -> int:
+    return int(lib().bass_attention_plan_bytes(ctypes.byref(desc)))
+
+
+def bass_attention_plan(desc, ctx_len, draft_len, flags, padded_len, plan, dev_status=None, stream=None):
+    torch = _torch()
+    if plan is None or not plan.is_cuda or not plan.is_contiguous():
+        raise ValueError("plan must be a contiguous GPU tensor")
+    _check(lib().bass_attention_plan(
+        ctypes.byref(desc), _dev(ctx_len, "ctx_len", torch.int32, (desc.B,)),
+        _dev(draft_len, "draft_len", torch.int32, (desc.B,)), ctypes.c_int32(int(flags)), ctypes.c_int32(int(padded_len)),
+        ctypes.c_void_p(plan.data_ptr()), ctypes.c_size_t(plan.numel() * plan.element_size()),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_attention_plan")
+
+
+def bass_attention_plan_host(desc, ctx_len, draft_len, flags=0, padded_len=0):
+    """Host planner: ctx_len / draft_len are host sequences of ints; returns (plan bytes as a numpy uint8 array,
+    host status word).  Needs no GPU."""
+    import numpy as np
+    cl = np.ascontiguousarray(np.asarray(ctx_len, dtype=np.int32))
+    dl = np.ascontiguousarray(np.asarray(draft_len, dtype=np.int32))
+    if cl.shape != (desc.B,) or dl.shape != (desc.B,):
+        raise ValueError("ctx_len and draft_len must have B entries")
+    nbytes = bass_attention_plan_bytes(desc)
+    buf = np.zeros(nbytes + 16, dtype=np.uint8)
+    off = (-buf.ctypes.data) % 16  # the entry point wants 16-byte alignment
+    plan = buf[off:off + nbytes]
+    status = ctypes.c_int32(0)
+    _check(lib().bass_attention_plan_host(
+        ctypes.byref(desc), ctypes.c_void_p(cl.ctypes.data), ctypes.c_void_p(dl.ctypes.data), ctypes.c_int32(int(flags)),
+        ctypes.c_int32(int(padded_len)), ctypes.c_void_p(plan.ctypes.data), ctypes.c_size_t(nbytes),
+        ctypes.cast(ctypes.byref(status), ctypes.c_void_p)), "bass_attention_plan_host")
+    return plan, int(status.value)
+
+
+def bass_verify_attention_planned(desc, Q, K_new, V_new, Kcache, Vcache, plan, O, lse, workspace, dev_status=None,
+                                  stream=None):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    rows = (desc.B, desc.kmax, desc.Hkv, desc.D)
+    et = _elt_dtype(desc)
+    if plan is None or not plan.is_cuda or not plan.is_contiguous():
+        raise ValueError("plan must be a contiguous GPU tensor")
+    if plan.numel() * plan.element_size() < bass_attention_plan_bytes(desc):
+        raise ValueError("plan holds fewer than bass_attention_plan_bytes(desc) bytes")
+    _check(lib().bass_verify_attention_planned(
+        ctypes.byref(desc), _dev(Q, "Q", et, qshape), _dev(K_new, "K_new", et, rows, optional=True),
+        _dev(V_new, "V_new", et, rows, optional=True), _cache_ptr(Kcache, desc, "Kcache"),
+        _cache_ptr(Vcache, desc, "Vcache"), ctypes.c_void_p(plan.data_ptr()),
+        *_result_args(desc, O, lse, workspace, dev_status, stream)), "bass_verify_attention_planned")
+
+
+def bass_bench_stream_read(K, V, bytes_each, waves, sink=None, stream=None) -> int:
+    """Plain streaming read of the first bytes_each bytes of the byte tensors K and V; returns the bytes read."""
+    for t, name in ((K, "K"), (V, "V")):
+        if t is None or not t.is_cuda or not t.is_contiguous() or t.numel() * t.element_size() < bytes_each:
+            raise ValueError(f"{name} must be a contiguous GPU tensor of at least bytes_each bytes")
+    r = int(lib().bass_bench_stream_read(ctypes.c_void_p(K.data_ptr()), ctypes.c_void_p(V.data_ptr()),
+                                         ctypes.c_size_t(int(bytes_each)), ctypes.c_int32(int(waves)),
+                                         _dev(sink, "sink", _torch().int32, optional=True), _stream(stream)))
+    _check(r if r < 0 else OK, "bass_bench_stream_read")
+    return r
+
+
+def alloc_plan(desc, device="cuda"):
+    """A plan buffer (bass_attention_plan fills it; it needs no clearing)."""
+    torch = _torch()
+    return torch.empty(bass_attention_plan_bytes(desc), dtype=torch.uint8, device=device)
 
 
 def bass_spec_accept(p, q, draft_tok, n_draft, u, n_accept, next_token, ctx_len=None, dev_status=None, stream=None):

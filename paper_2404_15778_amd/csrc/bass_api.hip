@@ -1,7 +1,7 @@
 // Version and status strings of libbass, and the host-side draft-length heuristic.
 #include "bass_common.h"
 
-extern "C" int bass_version(void) { return 121; /* 0.1.21: INT8 caches in the operand order of the integer score product */ }
+extern "C" int bass_version(void) { return 200; /* 0.2.0: step plans (bass_attention_plan) drive every attention launch */ }
 
 extern "C" const char* bass_status_string(int code) {
   switch (code) {

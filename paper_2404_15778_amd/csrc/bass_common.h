@@ -4,68 +4,16 @@
 #include <stdint.h>
 
 #include "bass.h"
+#include "attn_plan.h"
+#include "bass_layout.h"
 
 namespace bass {
 
 constexpr int kWave = 64;          // CDNA wavefront
-constexpr int kBlockTokens = 32;   // tokens per cache block (one PV contraction step of the bf16 MFMA)
-constexpr int kMaxWaves = 8192;    // upper bound of the attention work spread (sizes the workspace)
 // The registers of the streaming kernel allow one wavefront per SIMD (256 CUs x 4 SIMDs = 1024
 // resident wavefronts).  Measured on the paper-shaped batches, three quarters of that is fastest:
 // the memory system is saturated either way, and fewer wavefronts mean fewer partials to merge.
 constexpr int kDefaultWaves = 768;
-
-// ---------------------------------------------------------------------------------------
-// bf16 cache layout (library-owned).  A cache is [B][Hkv][nblk] blocks of 32 tokens; a block
-// holds 32*D bf16 stored in the order the matrix cores consume them, so that a wavefront
-// reads 1 KiB per load instruction (lane l reads bytes [16 l, 16 l + 16)) straight into an
-// MFMA operand.
-//   K block: [tile tt (2)][k-step t (D/32)][lane (64)][j (8)]
-//            lane = grp*16 + r holds token 16*tt + r, head elements d = 32*t + 8*grp + j
-//   V block: [d-tile mt (D/16)][lane (64)][j (8)]
-//            lane = grp*16 + dr holds head element d = 16*mt + dr of the eight tokens
-//            (j < 4: 4*grp + j ; j >= 4: 16 + 4*grp + (j-4))
-// The V token order is the order in which the score tile leaves the QK^T MFMA, which is why
-// the probabilities need no shuffle before the PV MFMA.
-// ---------------------------------------------------------------------------------------
-__host__ __device__ inline int num_blocks(int Lcap) { return (Lcap + kBlockTokens - 1) / kBlockTokens; }
-
-__host__ __device__ inline size_t k_elem_offset(int D, int tok_in_blk, int d) {
-  const int tt = tok_in_blk >> 4, r = tok_in_blk & 15;
-  const int t = d >> 5, grp = (d & 31) >> 3, j = d & 7;
-  return (size_t)(((tt * (D >> 5) + t) * 64 + grp * 16 + r) * 8 + j);
-}
-
-__host__ __device__ inline size_t v_elem_offset(int /*D*/, int tok_in_blk, int d) {
-  const int half = tok_in_blk >> 4, w = tok_in_blk & 15;
-  const int grp = w >> 2, j = half * 4 + (w & 3);
-  const int mt = d >> 4, dr = d & 15;
-  return (size_t)((mt * 64 + grp * 16 + dr) * 8 + j);
-}
-
-// ---------------------------------------------------------------------------------------
-// INT8 cache layout (BASS_DTYPE_INT8KV).  Same blocks of 32 tokens; a block holds the 32*D codes as
-// 16-byte chunks per lane, so that a wavefront still reads 1 KiB per load instruction, followed by the
-// block's 32 fp32 scales in token order (one per token of this kv head).
-//   K block: [tile tt (2)][k-step ks (D/64)][lane (64)][j (16)] -- the operand order of the INT8 matrix
-//            instruction (16x16x64): lane = grp*16 + r holds token 16*tt + r, head elements 64*ks + 16*grp + j
-//   V block: the element order of the bf16 V layout above, fragment mt of a lane being 8 codes = 8 bytes,
-//            two consecutive fragments per chunk: byte ((mt/2)*64 + lane)*16 + (mt%2)*8 + j
-// ---------------------------------------------------------------------------------------
-__host__ __device__ inline size_t i8_block_bytes(int D) { return (size_t)kBlockTokens * D + kBlockTokens * 4; }
-
-__host__ __device__ inline size_t i8_k_offset(int D, int tok_in_blk, int d) {
-  const int tt = tok_in_blk >> 4, r = tok_in_blk & 15;
-  const int ks = d >> 6, grp = (d & 63) >> 4, j = d & 15;
-  return (size_t)(((tt * (D >> 6) + ks) * 64 + grp * 16 + r) * 16 + j);
-}
-
-__host__ __device__ inline size_t i8_v_offset(int /*D*/, int tok_in_blk, int d) {
-  const int half = tok_in_blk >> 4, w = tok_in_blk & 15;
-  const int grp = w >> 2, j = half * 4 + (w & 3);
-  const int f = d >> 4, lane = grp * 16 + (d & 15);
-  return (size_t)(((f >> 1) * 64 + lane) * 16 + (f & 1) * 8 + j);
-}
 
 // Quantizer of the INT8 caches (see bass.h, BASS_DTYPE_INT8KV): every step is one fp32 operation.
 #ifdef __HIPCC__
@@ -146,18 +94,6 @@ __device__ inline uint64_t wave_sum_u64(uint64_t v) {  // the same total in ever
 }
 #endif
 
-// Per-sequence lengths with the clamping the header promises.  L = cached tokens before the
-// step, nq = query tokens; on return 0 <= nq <= kmax, 0 <= L, L + nq <= Lcap.
-__device__ inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {
-  bool bad = false;
-  if (nq < 0) { nq = 0; bad = true; }
-  if (nq > kmax) { nq = kmax; bad = true; }
-  if (nq > Lcap) { nq = Lcap; bad = true; }
-  if (L < 0) { L = 0; bad = true; }
-  if (L + nq > Lcap) { L = Lcap - nq; bad = true; }
-  return bad;
-}
-
 inline int check_desc(const bass_attn_desc* d) {
   if (!d) return BASS_ERR_INVALID_ARG;
   if (d->B <= 0 || d->kmax <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->D <= 0 || d->Lcap <= 0)
@@ -171,8 +107,60 @@ inline int check_desc(const bass_attn_desc* d) {
     return BASS_ERR_UNSUPPORTED;
   }
   // index arithmetic inside the kernels is 32-bit for block counts and 64-bit for bytes
-  if ((int64_t)d->B * d->Hkv * (int64_t)num_blocks(d->Lcap) >= (1ll << 30)) return BASS_ERR_UNSUPPORTED;
+  // (the flattened block list counts up to kMaxPad virtual blocks per unit on top of the real ones)
+  if ((int64_t)d->B * d->Hkv * ((int64_t)num_blocks(d->Lcap) + kMaxPad) >= (1ll << 30)) return BASS_ERR_UNSUPPORTED;
   return BASS_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Shape of an attention launch: which kernel serves the descriptor, over how many shares the block
+// list is divided, and the virtual blocks of a unit.  The plan of a step and the launches that
+// consume it derive it from the same inputs.
+// ---------------------------------------------------------------------------------------
+constexpr int kWavesPerWorkgroup = 4;
+constexpr int kAppendPad = 3;     // virtual blocks per unit when the append is fused (measured best: 3)
+constexpr int kPlainPad = 2;      // ... and when it is not (the unit's last blocks are the masked, slower ones)
+constexpr int kAppendBefore = 1;  // how many of those sit in front of the unit's last real block (one-tile matrix-core
+constexpr int kPlainBefore = 0;   // kernel; measured: +0.5 % with the fused append, slightly slower without)
+constexpr int kMaxStagedElems = 2048;  // kmax * D up to which the step's rows are appended inside the attention launch
+
+int attention_waves_setting();  // bass_set_attention_waves (0 = defaults); verify_attention.hip
+
+struct LaunchShape {
+  bool mfma;        // bf16 or INT8 caches: the matrix-core kernels
+  bool tiles;       // bf16 caches, more than one 16-row query tile per kv head: the workgroup-level kernel
+  bool fused_append;  // the step's rows are appended inside the attention launch
+  int rows_max, nwaves, nshares, pad, pad_before, fused_reduce;
+};
+
+// many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
+// launch merges the partials there, and a slightly wider spread measured best (896)
+// int8: INT8 caches; the kernel is bound by the conversion instructions there, not by memory, and
+// uses every SIMD (1024)
+inline int attention_waves(int setting, bool many_rows, bool int8) {
+  int w = setting > 0 ? setting : (int8 ? 1024 : many_rows ? 896 : kDefaultWaves);
+  if (w < 64) w = 64;
+  if (w > kMaxWaves) w = kMaxWaves;
+  return w - w % kWavesPerWorkgroup;
+}
+
+inline LaunchShape launch_shape(const bass_attn_desc* d, bool append) {
+  LaunchShape s;
+  const int setting = attention_waves_setting();
+  s.rows_max = d->kmax * (d->Hq / d->Hkv);
+  s.mfma = d->dtype != BASS_DTYPE_FP32;
+  s.tiles = d->dtype == BASS_DTYPE_BF16 && s.rows_max > 16;
+  s.fused_append = append && (d->dtype == BASS_DTYPE_FP32 || (int64_t)d->kmax * d->D <= kMaxStagedElems);
+  s.nwaves = attention_waves(setting, s.mfma && s.rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
+  // the workgroup-level kernel takes one stretch per workgroup (default 256, measured best: fewer
+  // partials to merge; a wavefront setting W gives W / 2)
+  s.nshares = !s.tiles ? s.nwaves : setting > 0 ? (s.nwaves / 2 > 16 ? s.nwaves / 2 : 16) : 256;
+  s.pad = s.fused_append ? kAppendPad : kPlainPad;
+  s.pad_before = 0;
+  if (s.mfma && s.rows_max <= 16) s.pad_before = s.fused_append ? kAppendBefore : kPlainBefore;
+  // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
+  s.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || s.rows_max <= 16) ? 1 : 0;
+  return s;
 }
 
 // Peek, so that the caller can still fetch the HIP error code after a BASS_ERR_HIP return.

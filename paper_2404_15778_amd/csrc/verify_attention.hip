@@ -31,9 +31,8 @@
 // stored in that token order, so P goes from accumulator to operand with a bf16 pack only.
 // Query rows of one kv head are (draft i, head-in-group) pairs, up to 64 rows = 4 tiles.
 #include <algorithm>
-#include <cstdio>
+#include <atomic>
 #include <type_traits>
-#include <cstdlib>
 
 #include "bass_common.h"
 
@@ -44,55 +43,15 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
-static int g_attention_waves = 0;  // 0 = default
-static int g_append_pad = 3;      // virtual blocks per unit when the append is fused (measured best: 3)
-static int g_plain_pad = 2;       // ... and when it is not (the unit's last blocks are the masked, slower ones)
-static int g_append_before = 1;   // how many of those sit in front of the unit's last real block (one-tile matrix-core
-static int g_plain_before = 0;    // kernel; measured: +0.5 % with the fused append, slightly slower without)
-static int g_wpw = 4;             // wavefronts per workgroup
-// Diagnostic build only (-DBASS_EXP_TRACE): every wavefront records wall-clock stamps of its phases
-// (schedule known, first fetch issued, first step done, streaming done, stores acknowledged, arrival
-// counted, delivered) and writes them into a caller's buffer of 16 int64 per wavefront when it is done.
-// The stamps wait in registers until then (low words, 10 ns ticks): a store in the middle of the kernel
-// would sit in the wait counts of the K/V fetches and change what is being measured.  The product build
-// compiles none of it.
-// Switched off: with the stamps added the one-tile kernel no longer fits its 512 registers (10 spilled
-// values) and one run of that build ended in a memory fault whose cause has not been found.  Until it
-// is, the diagnostic build must not be made or run.
-#ifdef BASS_EXP_TRACE
-#error "BASS_EXP_TRACE: this diagnostic build faulted on the GPU and the cause is not known; do not build it"
-static long long* g_trace = nullptr;
-#define BASS_TRACE_DECL() unsigned tr_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
-#define BASS_TRACE(slot) do { tr_[slot] = (unsigned)wall_clock64(); } while (0)
-#define BASS_TRACE_VAL(slot, v) do { tr_[slot] = (unsigned)(v); } while (0)
-#define BASS_TRACE_FLUSH() do { if (p.trace && lane == 0) { _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) p.trace[(size_t)w * 16 + i_] = tr_[i_]; } } while (0)
-#else
-#define BASS_TRACE_DECL() do { } while (0)
-#define BASS_TRACE(slot) do { } while (0)
-#define BASS_TRACE_VAL(slot, v) do { } while (0)
-#define BASS_TRACE_FLUSH() do { } while (0)
-#endif
-
-// many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
-// launch merges the partials there, and a slightly wider spread measured best (896)
-// int8: INT8 caches; the kernel is bound by the conversion instructions there, not by memory, and
-// uses every SIMD (1024)
-static int attention_waves(bool many_rows = false, bool int8 = false) {
-  int w = g_attention_waves > 0 ? g_attention_waves : (int8 ? 1024 : many_rows ? 896 : kDefaultWaves);
-  if (w < 64) w = 64;
-  if (w > kMaxWaves) w = kMaxWaves;
-  return w - w % g_wpw;
-}
+// Tuning knob of bass_set_attention_waves: process wide, read once per call.
+static std::atomic<int> g_attention_waves{0};  // 0 = defaults
+int attention_waves_setting() { return g_attention_waves.load(std::memory_order_relaxed); }
 
 struct AttnParams {
   int B, kmax, Hq, Hkv, D, Lcap, nblk_cap, g, rows_max, nwaves;
   unsigned g_magic;  // ceil(2^20 / g) if g <= 64 and rows_max <= 2048 (then r / g == (r * g_magic) >> 20 for every row r), else 0
   int wpw;  // wavefronts per workgroup of the attention launch (nwaves is a multiple)
   int nshares;  // stretches the block list is cut into: one per wavefront, or one per workgroup (tile kernel)
-  int pad;  // virtual blocks of every unit in the flattened list (see padded_blocks)
-  int pad_before;  // how many of them sit in front of the unit's last real block instead of behind it (see real_below)
-  int span;  // BASS-PAD variant: every active sequence is processed over at least this many cache
-             // positions (0: over its own length); the positions beyond its length are masked
   int fused_reduce;  // 1: the last-arriving wavefront merges a unit's partials; 0: a second launch does
   float scale_log2;  // scale * log2(e): scores are kept in the log2 domain
   const void* Q;
@@ -100,147 +59,66 @@ struct AttnParams {
   const void* Vc;
   const void* Knew;  // [B,kmax,Hkv,D] rows of this step to append first, or null
   const void* Vnew;
-  const int32_t* ctx_len;
-  const int32_t* draft_len;
+  // the step's plan (attn_plan.h): header, one record per share, the further segments, per-sequence
+  // query counts, per-unit contributors
+  const PlanHeader* plan;
+  int32_t signature;  // plan_signature() of the plan this launch expects
+  const ShareRecord* records;
+  const Segment* overflow;
+  const int32_t* seq_L;
+  const int32_t* seq_nq;
+  const int32_t* unit_owners;
   float* O;
   float* lse;
   float* part_acc;  // [slots][rows_max][D]
   float* part_ml;   // [slots][rows_max][2]  (running max in log2 units, running sum)
   int32_t* counters;  // [B*Hkv] partials delivered per unit; zero between calls
   int32_t* status;
-#ifdef BASS_EXP_TRACE
-  long long* trace;
-#endif
 };
 
 // Query row r of a kv head is query token r / g, head r % g of the group.  The division by the run-time
 // group size is a multiplication by a constant the host prepared (a generic integer division is some 35
-// instructions, and these sit on the way to the first fetch and on the way out).
+// instructions, and these sit on the way out).
 __device__ inline int row_token(const AttnParams& p, int r) {
   return p.g_magic ? (int)(((unsigned)r * p.g_magic) >> 20) : r / p.g;
 }
 
+__device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 // ---------------------------------------------------------------------------------------
-// Flattened schedule, recomputed by every wavefront from the device-side lengths.
+// The share of a wavefront (or workgroup), read from the step's plan.
 // ---------------------------------------------------------------------------------------
-// Inclusive prefix sum over the wavefront.  Shifts inside rows of 16 lanes are DPP moves (a few cycles
-// each; a generic shuffle goes through the LDS crossbar, ~100 cycles, and this scan sits on the path
-// from launch to the first K/V load); the three row totals are then added from scalar registers.
-template <int N>
-__device__ inline int row_shift_right(int v) {  // lane i of a row gets lane i - N of the row, 0 for i < N
-  return __builtin_amdgcn_update_dpp(0, v, 0x110 + N, 0xF, 0xF, true);
+// A segment whose address is the same in every lane, as wave-uniform values.
+__device__ inline Segment load_segment(const Segment* src) {
+  const i32x4 a = *(const i32x4*)src, b = *((const i32x4*)src + 1);
+  Segment g;
+  g.b = uniform(a[0]); g.kvh = uniform(a[1]); g.L = uniform(a[2]); g.nq = uniform(a[3]);
+  g.first = uniform(b[0]); g.n = uniform(b[1]); g.owners = uniform(b[2]); g.flags = uniform(b[3]);
+  return g;
 }
 
-__device__ inline int wave_incl_scan(int v, int lane) {
-  v += row_shift_right<1>(v);
-  v += row_shift_right<2>(v);
-  v += row_shift_right<4>(v);
-  v += row_shift_right<8>(v);
-  const int t0 = __builtin_amdgcn_readlane(v, 15);
-  const int t1 = __builtin_amdgcn_readlane(v, 31);
-  const int t2 = __builtin_amdgcn_readlane(v, 47);
-  const int row = lane >> 4;
-  return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
+// Segment si >= 1 of a share
+__device__ inline Segment later_segment(const AttnParams& p, const ShareRecord* rec, int overflow, int si) {
+  return load_segment(si == 1 ? &rec->seg[1] : p.overflow + overflow + (si - 2));
 }
 
-// Length of a unit in the flattened list = its real blocks plus p.pad virtual ones at its end.
-// A virtual block is no work; it stands for the fixed cost of the wavefront that handles the
-// unit's last blocks (with the fused append: copying the step's rows into the cache first), so
-// that this wavefront is handed correspondingly fewer real blocks and finishes with the others.
-__device__ inline int padded_blocks(const AttnParams& p, int nblk) { return nblk > 0 ? nblk + p.pad : 0; }
-
-// Where a unit's virtual blocks sit.  With all of them behind the last real block, the wavefront that holds
-// that block gets between none and all of the credit, depending on where the even cut falls, and the next
-// wavefront the rest.  With pb of them in front of the last real block and the others behind it, it gets
-// at least min(pb, pad - pb): its stretch reaches the last block through the ones in front or leaves it
-// through the ones behind.  A unit's entries are then: real blocks 0 .. nblk-2, pb virtual ones, the last
-// real block, pad - pb virtual ones.  (pb = 0 wherever stretches are not longer than a unit's pad, so that
-// no stretch can lie between two real blocks of a unit without holding one.)
-__device__ inline int real_below(int t, int nblk, int pb) {  // real blocks at entries below t, 0 <= t <= nblk + pad
-  return min(t, nblk - 1) + (t > nblk - 1 + pb ? 1 : 0);
+// The plan must have been made for this launch: same batch shape, same number of shares, and for a launch
+// that appends or does not; every record carries a signature of these.  Anything else (also a buffer that
+// holds no plan) stops the wavefront before it stores anything, with BASS_STATUS_PLAN_MISMATCH.
+__device__ inline bool record_matches(const AttnParams& p, const ShareRecord* rec) {
+  int sig = uniform(rec->signature);
+  asm volatile("" : "+s"(sig));  // keeps the comparison (and with it the wait for the record) where it is written
+  return sig == p.signature;
 }
-__device__ inline int entry_of(int j, int nblk, int pb) { return j < nblk - 1 ? j : j + pb; }  // entry of real block j
 
-__device__ inline int seq_blocks(const AttnParams& p, int b, int& L, int& nq, bool& bad) {
-  L = p.ctx_len[b];
-  nq = p.draft_len[b];
-  bad = clamp_lengths(L, nq, p.kmax, p.Lcap);
-  if (nq <= 0) return 0;
-  const int len = max(L + nq, min(p.span, p.Lcap));
-  return (len + kBlockTokens - 1) / kBlockTokens;
+__device__ inline void report_mismatch(const AttnParams& p, bool first_lane) {
+  if (first_lane && p.status) atomicOr(p.status, BASS_STATUS_PLAN_MISMATCH);
 }
 
 struct Unit {
   int b, kvh, L, nq;
-  int nblk;   // real blocks
-  int begin;  // flattened index of the unit's first block (units are padded_blocks() apart)
 };
-
-// The schedule of a call, held in registers: lane b keeps sequence b's lengths, padded block count
-// and inclusive prefix of it (first 64 sequences; later ones are re-read when needed).
-struct Sched {
-  int L, nq, nb, inc;
-  int total;  // sum over ALL sequences of blocks per kv head (wave-uniform)
-};
-
-__device__ inline Sched make_sched(const AttnParams& p, int lane, bool report) {
-  Sched s{0, 0, 0, 0, 0};
-  bool any_bad = false;
-  if (lane < p.B) s.nb = padded_blocks(p, seq_blocks(p, lane, s.L, s.nq, any_bad));
-  s.inc = wave_incl_scan(s.nb, lane);
-  s.total = __builtin_amdgcn_readlane(s.inc, 63);
-  for (int c0 = 64; c0 < p.B; c0 += 64) {
-    const int b = c0 + lane;
-    int L, nq, nb = 0;
-    bool bad = false;
-    if (b < p.B) nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
-    any_bad |= bad;
-    s.total += __builtin_amdgcn_readlane(wave_incl_scan(nb, lane), 63);
-  }
-  if (report && p.status && __any(any_bad) && lane == 0) atomicOr(p.status, BASS_STATUS_LEN_CLAMPED);
-  return s;
-}
-
-// Unit containing flattened block x (0 <= x < Hkv * total); wave-uniform.
-__device__ inline Unit locate(const AttnParams& p, const Sched& s, int x, int lane) {
-  Unit u{0, 0, 0, 0, 0, 0};
-  int c0 = 0, L = s.L, nq = s.nq, nb = s.nb, inc = s.inc;
-  while (true) {
-    const unsigned long long hit = __ballot((long long)inc * p.Hkv > (long long)x);
-    if (hit) {
-      const int src = __ffsll((long long)hit) - 1;
-      u.b = c0 + src;
-      u.L = __builtin_amdgcn_readlane(L, src);
-      u.nq = __builtin_amdgcn_readlane(nq, src);
-      const int npad = __builtin_amdgcn_readlane(nb, src);
-      u.nblk = npad - p.pad;
-      const int pre = __builtin_amdgcn_readlane(inc, src) - npad;
-      u.kvh = (x - pre * p.Hkv) / npad;
-      u.begin = pre * p.Hkv + u.kvh * npad;
-      return u;
-    }
-    const int running = __builtin_amdgcn_readlane(inc, 63);
-    c0 += 64;
-    if (c0 >= p.B) return u;  // not reached for x < Hkv * total
-    const int b = c0 + lane;
-    L = nq = nb = 0;
-    bool bad;
-    if (b < p.B) nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
-    inc = running + wave_incl_scan(nb, lane);
-  }
-}
-
-// Even division of the flattened block list: wavefronts 0 .. rem-1 take per + 1 consecutive blocks,
-// the others per (every wavefront works, and no share is more than one block longer than another).
-struct Split {
-  int per, rem;
-  __device__ int first(int w) const { return w * per + min(w, rem); }  // first block of wavefront w
-  __device__ int owner(int x) const {                                   // wavefront that holds block x
-    const int big = rem * (per + 1);
-    return x < big ? x / (per + 1) : rem + (x - big) / max(per, 1);
-  }
-};
-__device__ inline Split make_split(int total, int nwaves) { return Split{total / nwaves, total % nwaves}; }
+__device__ inline Unit unit_of(const Segment& g) { return Unit{g.b, g.kvh, g.L, g.nq}; }
 
 // Partials travel between wavefronts that may sit on different XCDs, whose L2 caches are not
 // coherent with each other for ordinary accesses.  Instead of device-scope fences (which write
@@ -340,8 +218,6 @@ struct CombineJob {
   Unit u;
   int w_lo, w_hi;
 };
-
-__device__ inline int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // 2 GiB: larger than any descriptor, and adding a partial's offset, which the host keeps below
 // 2 GiB, cannot wrap around.
@@ -505,18 +381,15 @@ __device__ inline void combine_jobs(const AttnParams& p, const CombineJob& ja, b
 }
 
 // All of this wavefront's partial stores have reached the device-coherent level once their
-// acknowledgements are back; only then may its arrival be counted.
-__device__ inline void partial_stores_done() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+// acknowledgements are back (the sc1 stores are written through; the vector-memory counter of this
+// wavefront falls to zero only when every one of them has been acknowledged); only then may its
+// arrival be counted.  The wait is spelled out: a workgroup-scope fence is lowered without it.
+__device__ inline void partial_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Counts this wavefront's arrival at one or two units (after partial_stores_done).  A job's
 // `last` result is true if this wavefront delivered the unit's last partial: it then owns the
 // reduction over wavefronts w_lo..w_hi.  Both counters are bumped before either result is awaited.
-// The wavefronts that hold a unit's first and last block (integer divisions: callers do this while their
-// first fetches are under way, not on the way out).
-__device__ inline void set_owners(const Split& sp, CombineJob& j, int pb = 0) {
-  j.w_lo = sp.owner(j.u.begin + entry_of(0, j.u.nblk, pb));
-  j.w_hi = sp.owner(j.u.begin + entry_of(j.u.nblk - 1, j.u.nblk, pb));
-}
+__device__ inline CombineJob job_of(const Segment& g) { return CombineJob{unit_of(g), seg_w_lo(g), seg_w_hi(g)}; }
 
 __device__ inline int32_t* arrival_counter(const AttnParams& p, CombineJob& j, int& nparts) {
   nparts = j.w_hi - j.w_lo + 1;
@@ -540,22 +413,16 @@ __device__ inline void arrive(const AttnParams& p, int lane, CombineJob& ja, boo
 }
 
 // Query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse.
-// Wavefront w clears them for the units w, w + nwaves, ... at the start of the kernel.
+// Wavefront w clears them for the units w, w + nw, ...
 // kInactiveOnly: only the units of sequences without query tokens (they have no blocks, hence no
 // wavefront of their own); the caller then clears the unused rows of the other units elsewhere (the
 // one-tile matrix-core kernel: by the wavefront that holds the unit's last block).
 template <int DC, bool kInactiveOnly = false>
-__device__ inline void zero_unused_rows(const AttnParams& p, const Sched& s, int w, int nw, int lane) {
+__device__ inline void zero_unused_rows(const AttnParams& p, int w, int nw, int lane) {
+  if (kInactiveOnly && !p.plan->any_inactive) return;
   for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
     const int b = unit / p.Hkv;
-    int nq;
-    if (b < 64) {
-      nq = __builtin_amdgcn_readlane(s.nq, b);
-    } else {
-      int L;
-      bool bad;
-      seq_blocks(p, b, L, nq, bad);
-    }
+    const int nq = uniform(p.seq_nq[b]);
     if (!kInactiveOnly || nq == 0) zero_rows<DC>(p, b, unit - b * p.Hkv, nq * p.g, lane);
   }
 }
@@ -671,7 +538,6 @@ struct NewRows {
 // The host keeps kmax * D <= kMaxStagedElems so that a workgroup's slices fit in 64 KiB of LDS.
 constexpr int kStageLoads = 2;
 constexpr int kStagePass = kStageLoads * 64;
-constexpr int kMaxStagedElems = 2048;
 
 struct StageRegs {
   u32x4 k[kStageLoads], v[kStageLoads];
@@ -1088,57 +954,43 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   // sit in the ring's wait counts.)
   constexpr bool kPair = (NT == 1);
   const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * p.wpw + (threadIdx.x >> 6);
+  const int w = uniform(blockIdx.x * p.wpw + (threadIdx.x >> 6));
   const int col = lane & 15, grp = lane >> 4;
-  BASS_TRACE_DECL();
-  BASS_TRACE(0);
 
-  const Sched sched = make_sched(p, lane, w == 0);
-  BASS_TRACE(13);
-  const int total = sched.total * p.Hkv;
-  const Split sp = make_split(total, p.nshares);
-  int x = sp.first(w);
-  const int x_end = sp.first(w + 1);
-  const int pb = sp.per > p.pad ? p.pad_before : 0;  // see real_below
-  // Unused query rows: those of inactive sequences here; those of a unit by the wavefront that holds the
-  // unit's last block, right before its partial stores (that wavefront is handed fewer real blocks, and
-  // the stores are then acknowledged together with the partials instead of holding up the first fetch).
-  zero_unused_rows<D, true>(p, sched, w, p.nwaves, lane);
-  BASS_TRACE(1);
-
-  while (x < x_end) {
-    BASS_TRACE(9);
-    const Unit uA = locate(p, sched, x, lane);
-    BASS_TRACE(10);
-    const int spanA = min(x_end, uA.begin + uA.nblk + p.pad) - x;  // our stretch of unit A, virtual blocks included
-    const int firstA = real_below(x - uA.begin, uA.nblk, pb);         // our first real block of unit A ...
-    const int nA = real_below(x - uA.begin + spanA, uA.nblk, pb) - firstA;  // ... and how many
-    if (nA <= 0) {  // only virtual blocks of this unit fall into our share
-      x += spanA;
-      continue;
-    }
-    // the share's first block is fetched right away; what follows (the second unit, the queries, the
-    // rows of a fused append, ...) runs while that fetch is under way
-    const ptrdiff_t vecA = (((ptrdiff_t)uA.b * p.Hkv + uA.kvh) * p.nblk_cap + firstA) * kBlkVec;
+  // This wavefront's share: the first two segments come with the record, in one round trip; the plan's
+  // header travels at the same time.  Nothing waits for either before the first K/V fetch needs its
+  // address: what the loop below sets up once (constants, lane offsets) runs under that round trip.
+  const ShareRecord* rec = p.records + w;
+  Segment sa = load_segment(&rec->seg[0]);
+  Segment sb = load_segment(&rec->seg[1]);
+  int nseg_plan = uniform(rec->nseg), overflow = uniform(rec->overflow);
+  __builtin_amdgcn_sched_barrier(0);  // the loads above are issued here, whatever is scheduled below
+  bool ok;
+  int nseg;
+  int si = 0;
+  do {
+    // The first fetch is issued before the plan has been checked, so its address is forced into the
+    // cache whatever the record holds (a buffer without a plan must not turn into a wild read); stores
+    // and everything else wait for the check.
+    const int firstA = min(max(sa.first, 0), p.nblk_cap - 1);
+    const ptrdiff_t unitA = (ptrdiff_t)min(max(sa.b, 0), p.B - 1) * p.Hkv + min(max(sa.kvh, 0), p.Hkv - 1);
+    const ptrdiff_t vecA = (unitA * p.nblk_cap + firstA) * kBlkVec;
     const uint4* kc = (const uint4*)p.Kc;
     const uint4* vc = (const uint4*)p.Vc;
     Regs r0;
     if constexpr (kI8) load_block_i8<D>(r0, kc + vecA, vc + vecA, lane, grp);
     else load_block<D>(r0, kc + vecA + lane, vc + vecA + lane);
-    BASS_TRACE(15);
-    Unit uB = uA;
-    int nB = 0, spanB = 0;
-    bool hasB = false;
-    if constexpr (kPair) {
-      if (x + spanA < x_end) {
-        hasB = true;
-        uB = locate(p, sched, x + spanA, lane);  // starts at its block 0
-        spanB = min(x_end, uB.begin + uB.nblk + p.pad) - (x + spanA);
-        nB = real_below(spanB, uB.nblk, pb);
-      }
-    }
+    ok = record_matches(p, rec);
+    asm volatile("" : "+s"(nseg_plan), "+s"(overflow));  // as in record_matches: no use of the record ahead of the loop
+    nseg = ok ? nseg_plan : 0;
+    if (si >= nseg) break;  // an idle wavefront, or no plan for this launch
+    const Unit uA = unit_of(sa);
+    const int nA = sa.n;  // our real blocks of unit A: firstA .. firstA + nA - 1
+    const bool hasB = kPair && si + 1 < nseg;
+    const Unit uB = hasB ? unit_of(sb) : uA;
+    const int firstB = hasB ? sb.first : 0, nB = hasB ? sb.n : 0;
+    const bool lastA = (sa.flags & kSegLast) != 0, lastB = hasB && (sb.flags & kSegLast) != 0;  // we hold the unit's last block
     const int n = nA + nB;
-    BASS_TRACE(2);
 
     typename std::conditional<kI8, QFragI8<D, NT>, QFrag<D, NT>>::type qc, qB;
     if constexpr (kI8) {
@@ -1150,9 +1002,8 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     }
     RowState<D, NT> st, parked;
     clear_state<D, NT>(st);
-    CombineJob ja{uA, 0, 0}, jb{uB, 0, 0};  // who else contributes to our units: needed at the very end only
-    set_owners(sp, ja, pb);
-    set_owners(sp, jb, pb);
+    CombineJob ja = job_of(sa), jb = ja;  // who else contributes to our units
+    if (hasB) jb = job_of(sb);
     int cur_L = uA.L, cur_valid = uA.L + uA.nq, cur_blk = firstA;  // block index = cur_blk + s
 
     // fused append: the units whose new tokens lie in our blocks get their rows staged in LDS
@@ -1167,7 +1018,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
                        uB.L, uB.nq};
     NewRows cur_new = newA;
     const bool stageA = fused && uA.nq > 0 && (firstA + nA) * kBlockTokens > uA.L;
-    const bool stageB = fused && hasB && uB.nq > 0 && nB * kBlockTokens > uB.L;
+    const bool stageB = fused && hasB && uB.nq > 0 && (firstB + nB) * kBlockTokens > uB.L;
     // one set of staging registers: a share that holds the new tokens of both its units is rare (the
     // second unit then lies wholly inside the share) and stages the second unit's rows afterwards
     const bool stage1 = stageA || stageB;
@@ -1195,7 +1046,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     };
 
     // element offsets (in uint4) of step s inside the K and V caches
-    const ptrdiff_t vecB = (((ptrdiff_t)uB.b * p.Hkv + uB.kvh) * p.nblk_cap - nA) * kBlkVec;
+    const ptrdiff_t vecB = (((ptrdiff_t)uB.b * p.Hkv + uB.kvh) * p.nblk_cap + firstB - nA) * kBlkVec;
 
     // Every fetch is issued unconditionally so that the wait counts before each compute step are
     // exact (a fetch under a branch would force a wait for ALL outstanding loads at the join and
@@ -1220,7 +1071,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
           qc = qB;
           cur_L = uB.L;
           cur_valid = uB.L + uB.nq;
-          cur_blk = -nA;
+          cur_blk = firstB - nA;
           cur_new = newB;
         }
       }
@@ -1255,7 +1106,6 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
-        if (s == 0) BASS_TRACE(8);
         fetch(r0, s + 3);
         if (s + 1 < n) step(r1, s + 1);
         fetch(r1, s + 4);
@@ -1275,30 +1125,30 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         if (s + 1 < n) step(r1, s + 1);
       }
     }
-    BASS_TRACE(3);
-    BASS_TRACE_VAL(11, (hasB ? 1 : 0) + (fused && ((firstA + nA) * kBlockTokens > uA.L || (hasB && nB * kBlockTokens > uB.L)) ? 2 : 0) + 4 * n);
-    BASS_TRACE_VAL(12, __builtin_amdgcn_s_getreg(6164));  // XCC_ID
-
-    if (firstA + nA == uA.nblk) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
-    if (hasB && nB == uB.nblk) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
+    if (lastA) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
+    if (lastB) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
-    if (!p.fused_reduce) {  // a second launch merges the partials
-      BASS_TRACE_FLUSH();
-      x += spanA + spanB;
-      continue;
+    if (p.fused_reduce) {  // otherwise a second launch merges the partials
+      partial_stores_done();
+      bool mergeA, mergeB;
+      arrive(p, lane, ja, mergeA, hasB, jb, mergeB);
+      if (mergeA || mergeB) combine_jobs<D>(p, ja, mergeA, jb, mergeB, lane);
     }
-    partial_stores_done();
-    BASS_TRACE(4);
-    bool lastA, lastB;
-    arrive(p, lane, ja, lastA, hasB, jb, lastB);
-    BASS_TRACE(5);
-    BASS_TRACE_VAL(7, (lastA ? 1 : 0) + (lastB ? 2 : 0));
-    if (lastA || lastB) combine_jobs<D>(p, ja, lastA, jb, lastB, lane);
-    BASS_TRACE(6);
-    BASS_TRACE_FLUSH();
-    x += spanA + spanB;
+    si += hasB ? 2 : 1;
+    if (si < nseg) {  // shares that touch more units than the record holds
+      sa = later_segment(p, rec, overflow, si);
+      if (kPair && si + 1 < nseg) sb = later_segment(p, rec, overflow, si + 1);
+    }
+  } while (si < nseg);
+  if (!ok) {
+    report_mismatch(p, w == 0 && lane == 0);
+    return;
   }
+  // Unused query rows of inactive sequences (those of an active one are cleared by the wavefront that
+  // holds the unit's last block, right before its partial stores: that wavefront is handed fewer real
+  // blocks, and the stores are acknowledged together with the partials)
+  zero_unused_rows<D, true>(p, w, p.nwaves, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1327,12 +1177,13 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
   const int wg = blockIdx.x;  // the stretch of this workgroup
   const int row0 = 16 * wv;
 
-  const Sched sched = make_sched(p, lane, wg == 0 && wv == 0);
-  const int total = sched.total * p.Hkv;
-  const Split sp = make_split(total, p.nshares);
-  int x = sp.first(wg);
-  const int x_end = sp.first(wg + 1);
-  zero_unused_rows<D>(p, sched, wg * 4 + wv, 4 * p.nshares, lane);
+  const ShareRecord* rec = p.records + wg;
+  const int nseg = uniform(rec->nseg), overflow = uniform(rec->overflow);
+  if (!record_matches(p, rec)) {
+    report_mismatch(p, wg == 0 && threadIdx.x == 0);
+    return;
+  }
+  zero_unused_rows<D>(p, wg * 4 + wv, 4 * p.nshares, lane);
 
   const uint4* kc = (const uint4*)p.Kc;
   const uint4* vc = (const uint4*)p.Vc;
@@ -1340,20 +1191,16 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
     uint4 k[kLoads], v[kLoads];
   };
 
-  while (x < x_end) {
-    const Unit u = locate(p, sched, x, lane);
-    const int span = min(x_end, u.begin + u.nblk + p.pad) - x;  // our stretch of the unit, virtual blocks included
-    const int n = min(span, u.begin + u.nblk - x);               // its real blocks
-    if (n <= 0) {
-      x += span;
-      continue;
-    }
+  for (int si = 0; si < nseg; ++si) {
+    const Segment seg = si == 0 ? load_segment(&rec->seg[0]) : later_segment(p, rec, overflow, si);
+    const Unit u = unit_of(seg);
+    const int n = seg.n;  // real blocks seg.first .. seg.first + n - 1 of the unit
     const bool active = row0 < u.nq * p.g;  // this wavefront owns a query tile of the unit
     QFrag<D, 1> q;
     load_queries<D, 1>(p, u, active, col, grp, q, row0);
     RowState<D, 1> st;
     clear_state<D, 1>(st);
-    const int blk0 = x - u.begin;
+    const int blk0 = seg.first;
     const ptrdiff_t vec0 = (((ptrdiff_t)u.b * p.Hkv + u.kvh) * p.nblk_cap + blk0) * kBlkVec;
     const int mine = wv * kQuarter + lane;  // first uint4 this lane moves
 
@@ -1431,7 +1278,6 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
       for (int j = 0; j < kTileAhead; ++j) step(g[j], s + j);
     }
     if (active) store_partial<D, 1>(p, u, wg, st, col, grp, row0);
-    x += span;
   }
 }
 
@@ -1450,36 +1296,11 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   const int sweep = (int)(item % sweeps);
   const int unit = (int)(item / sweeps);
   const int b = unit / p.Hkv, kvh = unit % p.Hkv;
-  const Sched sched = make_sched(p, lane, false);
-  // first block of the unit in the flattened list: blocks of earlier sequences, then earlier heads
-  int L, nq, nb;
-  if (b < 64) {
-    L = __builtin_amdgcn_readlane(sched.L, b);
-    nq = __builtin_amdgcn_readlane(sched.nq, b);
-    nb = __builtin_amdgcn_readlane(sched.nb, b);
-  } else {
-    bool bad;
-    nb = padded_blocks(p, seq_blocks(p, b, L, nq, bad));
-  }
-  if (nb == 0 || 4 * sweep >= nq * p.g) return;
-  int before = 0;  // padded blocks of sequences 0..b-1
-  if (b < 64) {
-    before = __builtin_amdgcn_readlane(sched.inc, b) - nb;
-  } else {
-    before = __builtin_amdgcn_readlane(sched.inc, 63);
-    for (int c0 = 64; c0 < b; c0 += 64) {
-      const int bb = c0 + lane;
-      int L2, nq2, nb2 = 0;
-      bool bad;
-      if (bb < b) nb2 = padded_blocks(p, seq_blocks(p, bb, L2, nq2, bad));
-      before += __builtin_amdgcn_readlane(wave_incl_scan(nb2, lane), 63);
-    }
-  }
-  CombineJob job;
-  job.u = Unit{b, kvh, L, nq, nb - p.pad, before * p.Hkv + kvh * nb};
-  const Split sp = make_split(sched.total * p.Hkv, p.nshares);
-  job.w_lo = sp.owner(job.u.begin);
-  job.w_hi = sp.owner(job.u.begin + job.u.nblk - 1);
+  if (!record_matches(p, p.records)) return;  // reported by the attention launch
+  const int nq = uniform(p.seq_nq[b]);
+  if (nq == 0 || 4 * sweep >= nq * p.g) return;
+  const int owners = uniform(p.unit_owners[unit]);
+  CombineJob job{Unit{b, kvh, uniform(p.seq_L[b]), nq}, owners & 0xFFFF, (owners >> 16) & 0xFFFF};
   CombineRegs<KC> regs;
   combine_issue<KC, DC>(p, job, 4 * sweep, lane, regs);
   combine_finish<KC, DC>(p, job, lane, regs);
@@ -1494,31 +1315,27 @@ constexpr int kRowChunk = 8;
 
 __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
   const int lane = threadIdx.x & 63;
-  const int w = blockIdx.x * p.wpw + (threadIdx.x >> 6);
+  const int w = uniform(blockIdx.x * p.wpw + (threadIdx.x >> 6));
   const int D = p.D;
   const int nd = (D + 63) / 64;  // head elements per lane (<= 4)
 
-  const Sched sched = make_sched(p, lane, w == 0);
-  const int total = sched.total * p.Hkv;
-  const Split sp = make_split(total, p.nshares);
-  int x = sp.first(w);
-  const int x_end = sp.first(w + 1);
-  zero_unused_rows<0>(p, sched, w, p.nwaves, lane);
+  const ShareRecord* rec = p.records + w;
+  const int nseg = uniform(rec->nseg), overflow = uniform(rec->overflow);
+  if (!record_matches(p, rec)) {
+    report_mismatch(p, w == 0 && lane == 0);
+    return;
+  }
+  zero_unused_rows<0>(p, w, p.nwaves, lane);
 
-  while (x < x_end) {
-    const Unit u = locate(p, sched, x, lane);
-    const int blk0 = x - u.begin;
-    const int span = min(x_end, u.begin + u.nblk + p.pad) - x;
-    const int nseg = min(span, u.begin + u.nblk - x);
-    if (nseg <= 0) {  // only virtual blocks of this unit fall into our share
-      x += span;
-      continue;
-    }
+  for (int si = 0; si < nseg; ++si) {
+    const Segment seg = si == 0 ? load_segment(&rec->seg[0]) : later_segment(p, rec, overflow, si);
+    const Unit u = unit_of(seg);
+    const int blk0 = seg.first, nseg_blocks = seg.n;
     const int rows = u.nq * p.g;
     const int n_valid = u.L + u.nq;
     const int tok_lo = blk0 * kBlockTokens;
-    const int tok_hi = min(n_valid, (blk0 + nseg) * kBlockTokens);
-    if (p.Knew && append_own_rows_fp32(p, u, blk0, nseg, lane)) partial_stores_done();
+    const int tok_hi = min(n_valid, (blk0 + nseg_blocks) * kBlockTokens);
+    if (p.Knew && append_own_rows_fp32(p, u, blk0, nseg_blocks, lane)) partial_stores_done();
     const float* kbase = (const float*)p.Kc + ((size_t)u.b * p.Hkv + u.kvh) * p.Lcap * D;
     const float* vbase = (const float*)p.Vc + ((size_t)u.b * p.Hkv + u.kvh) * p.Lcap * D;
     const size_t slot = (size_t)w + (size_t)u.b * p.Hkv + u.kvh;
@@ -1600,118 +1417,96 @@ __global__ __launch_bounds__(256) void verify_attn_fp32(AttnParams p) {
       }
     }
     partial_stores_done();
-    CombineJob job{u, 0, 0};
-    set_owners(sp, job);
+    CombineJob job = job_of(seg);
     bool last, unused;
     arrive(p, lane, job, last, false, job, unused);
     if (last) combine_jobs<0>(p, job, true, job, false, lane);
-    x += span;
   }
 }
 
-// Workspace = [unit counters, padded to 256 B][partial outputs][partial (max, sum) pairs].
-static size_t counter_bytes(const bass_attn_desc* d) {
-  return (((size_t)d->B * d->Hkv * sizeof(int32_t)) + 255) & ~(size_t)255;
+// Workspace = [unit counters, padded to 256 B][the plan of calls that bring none][partial outputs]
+// [partial (max, sum) pairs], laid out for `shares` stretches.
+struct Workspace {
+  size_t plan, part_acc, part_ml, bytes;
+};
+
+static Workspace workspace_layout(const bass_attn_desc* d, int shares) {
+  Workspace w;
+  const size_t slots = (size_t)shares + (size_t)d->B * d->Hkv;
+  const size_t rows = (size_t)d->kmax * (d->Hq / d->Hkv);
+  w.plan = (((size_t)d->B * d->Hkv * sizeof(int32_t)) + 255) & ~(size_t)255;
+  w.part_acc = w.plan + plan_layout(d->B, d->Hkv, shares).bytes;
+  w.part_ml = w.part_acc + slots * rows * (size_t)d->D * sizeof(float);
+  w.bytes = w.part_ml + slots * rows * 2 * sizeof(float);
+  return w;
 }
 
-static size_t workspace_bytes(const bass_attn_desc* d) {
-  const size_t slots = (size_t)kMaxWaves + (size_t)d->B * d->Hkv;
-  const size_t rows = (size_t)d->kmax * (d->Hq / d->Hkv);
-  return counter_bytes(d) + slots * rows * ((size_t)d->D + 2) * sizeof(float);
-}
+PlanShape plan_shape(const bass_attn_desc* d, const LaunchShape& ls, int span);
+int launch_plan(const bass_attn_desc* d, const LaunchShape& ls, int span, const int32_t* ctx_len, const int32_t* draft_len,
+                void* plan, int32_t* dev_status, void* stream, int32_t* clear_counters);
 
 }  // namespace bass
 
-#ifdef BASS_EXP_TRACE
-extern "C" void bass_debug_set_trace(void* ptr) { bass::g_trace = (long long*)ptr; }
-#endif
-
-#ifdef BASS_EXP_TRACE
-extern "C" void bass_debug_set_pad(int pad) { bass::g_append_pad = pad; bass::g_plain_pad = pad; }
-#endif
-
 extern "C" int bass_set_attention_waves(int waves) {
-  bass::g_attention_waves = waves > 0 ? waves : 0;
-  return bass::attention_waves();
+  bass::g_attention_waves.store(waves > 0 ? waves : 0, std::memory_order_relaxed);
+  return bass::attention_waves(bass::attention_waves_setting(), false, false);
 }
 
 extern "C" size_t bass_verify_attention_workspace_bytes(const bass_attn_desc* d) {
   if (bass::check_desc(d) != BASS_OK) return 0;
-  return bass::workspace_bytes(d);
+  return bass::workspace_layout(d, bass::kMaxWaves).bytes;
 }
 
 namespace bass {
 
-// BASS_ATTN_PAD="<fused>,<plain>[,<wavefronts per workgroup>[,<in front, fused>,<in front, plain>]]" overrides the
-// virtual blocks per unit and where they sit (tuning experiments).
-static void read_pad_override() {
-  static bool done = false;
-  if (done) return;
-  done = true;
-  if (const char* e = getenv("BASS_ATTN_PAD")) {
-    int a = -1, b = -1, c = 4, fa = g_append_before, fb = g_plain_before;
-    if (sscanf(e, "%d,%d,%d,%d,%d", &a, &b, &c, &fa, &fb) >= 2 && a >= 0 && a <= 8 && b >= 0 && b <= 8 && c >= 1 && c <= 4 &&
-        fa >= 0 && fb >= 0) {
-      g_append_pad = a;
-      g_plain_pad = b;
-      g_append_before = fa < a ? fa : a;
-      g_plain_before = fb < b ? fb : b;
-      g_wpw = c;
-    }
-  }
-}
-
-static int launch_attention(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
-                            const void* Kcache, const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
-                            float* O, float* lse, void* workspace, size_t workspace_bytes, int32_t* dev_status,
-                            void* stream, int span = 0) {
-  int rc = check_desc(d);
-  if (rc != BASS_OK) return rc;
-  if (!Q || !Kcache || !Vcache || !ctx_len || !draft_len || !O || !workspace) return BASS_ERR_INVALID_ARG;
+static int check_attention_args(const bass_attn_desc* d, const LaunchShape& ls, const void* Q, const void* K_new,
+                                const void* V_new, const void* Kcache, const void* Vcache, const float* O,
+                                const void* workspace) {
+  if (!Q || !Kcache || !Vcache || !O || !workspace) return BASS_ERR_INVALID_ARG;
   if ((K_new == nullptr) != (V_new == nullptr)) return BASS_ERR_INVALID_ARG;
   if (((uintptr_t)workspace & 15) != 0) return BASS_ERR_INVALID_ARG;
-  const int g = d->Hq / d->Hkv;
-  const int rows_max = d->kmax * g;
-  const bool mfma = d->dtype != BASS_DTYPE_FP32;  // bf16 or INT8 caches: the matrix-core kernel
-  if (mfma && rows_max > 64) return BASS_ERR_UNSUPPORTED;
+  if (ls.mfma && ls.rows_max > 64) return BASS_ERR_UNSUPPORTED;
   // partials of one unit are addressed with 32-bit byte offsets
-  if ((int64_t)rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
-  if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  if ((int64_t)ls.rows_max * d->D * 4 * kMaxWaves >= (1ll << 31)) return BASS_ERR_UNSUPPORTED;
+  return BASS_OK;
+}
 
-  read_pad_override();
+// The attention launch (and, with many query rows per kv head, the merge launch) for a plan that lies at
+// `plan`, made for the shape `ls`; K_new / V_new: the rows a fused append puts into the caches, or null.
+static int launch_attention(const bass_attn_desc* d, const LaunchShape& ls, const void* Q, const void* K_new,
+                            const void* V_new, const void* Kcache, const void* Vcache, const void* plan, float* O,
+                            float* lse, const Workspace& wl, void* workspace, int32_t* dev_status, void* stream) {
+  const int g = d->Hq / d->Hkv;
+  const int rows_max = ls.rows_max;
   AttnParams p;
   p.B = d->B; p.kmax = d->kmax; p.Hq = d->Hq; p.Hkv = d->Hkv; p.D = d->D; p.Lcap = d->Lcap;
   p.nblk_cap = num_blocks(d->Lcap); p.g = g; p.rows_max = rows_max;
   p.g_magic = (g <= 64 && rows_max <= 2048) ? ((1u << 20) + (unsigned)g - 1u) / (unsigned)g : 0u;  // exact there: checked exhaustively
-  p.nwaves = attention_waves(mfma && rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
-  // bf16 caches, more than one query tile per kv head: the workgroup-level kernel, one stretch per
-  // workgroup (default 256, measured best: fewer partials to merge; a wavefront setting W gives W / 2)
-  const bool tiles = d->dtype == BASS_DTYPE_BF16 && rows_max > 16;
-  p.nshares = !tiles ? p.nwaves : g_attention_waves > 0 ? std::max(16, p.nwaves / 2) : 256;
-  p.pad = K_new ? g_append_pad : g_plain_pad;
-  p.pad_before = 0;  // set below for the kernel that supports it
-  p.span = span;
-  // one query tile per kv head: the last-arriving wavefront reduces; more: a second, chip-wide launch
-  p.fused_reduce = (d->dtype == BASS_DTYPE_FP32 || rows_max <= 16) ? 1 : 0;
-  if (mfma && rows_max <= 16) p.pad_before = std::min(p.pad, K_new ? g_append_before : g_plain_before);
+  p.nwaves = ls.nwaves;
+  p.nshares = ls.nshares;
+  p.fused_reduce = ls.fused_reduce;
   p.scale_log2 = d->scale * 1.4426950408889634f;
   p.Q = Q; p.Kc = Kcache; p.Vc = Vcache; p.Knew = K_new; p.Vnew = V_new;
-  p.ctx_len = ctx_len; p.draft_len = draft_len;
+  const PlanLayout pl = plan_layout(d->B, d->Hkv, ls.nshares);
+  const char* pb = (const char*)plan;
+  p.plan = (const PlanHeader*)pb;
+  p.signature = plan_signature(d->B, d->kmax, d->Hkv, d->Lcap, ls.nshares, K_new ? kPlanAppend : 0);
+  p.records = (const ShareRecord*)(pb + pl.records);
+  p.overflow = (const Segment*)(pb + pl.overflow);
+  p.seq_L = (const int32_t*)(pb + pl.seq_L);
+  p.seq_nq = (const int32_t*)(pb + pl.seq_nq);
+  p.unit_owners = (const int32_t*)(pb + pl.unit_owners);
   p.O = O; p.lse = lse; p.status = dev_status;
-#ifdef BASS_EXP_TRACE
-  p.trace = g_trace;
-#endif
-  const size_t slots = (size_t)kMaxWaves + (size_t)d->B * d->Hkv;
   p.counters = (int32_t*)workspace;
-  p.part_acc = (float*)((char*)workspace + counter_bytes(d));
-  p.part_ml = p.part_acc + slots * rows_max * d->D;
+  p.part_acc = (float*)((char*)workspace + wl.part_acc);
+  p.part_ml = (float*)((char*)workspace + wl.part_ml);
 
   hipStream_t s = (hipStream_t)stream;
-  p.wpw = g_wpw;
+  p.wpw = kWavesPerWorkgroup;
   const dim3 grid(p.nwaves / p.wpw), block(64 * p.wpw);
   if (d->dtype == BASS_DTYPE_FP32) {
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);
-  } else if (tiles) {
+  } else if (ls.tiles) {
     const dim3 tgrid((unsigned)p.nshares), tblock(256);
     if (d->D == 128) {
       if (K_new) hipLaunchKernelGGL((verify_attn_tiles_bf16<128, true>), tgrid, tblock, 0, s, p);
@@ -1754,13 +1549,32 @@ static int launch_attention(const bass_attn_desc* d, const void* Q, const void* 
   return launch_status();
 }
 
+// Plan (into the workspace) and attention in one call.
+static int plan_and_launch(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
+                           const void* Kcache, const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                           float* O, float* lse, void* workspace, size_t workspace_bytes, int32_t* dev_status,
+                           void* stream, int span = 0) {
+  int rc = check_desc(d);
+  if (rc != BASS_OK) return rc;
+  if (!ctx_len || !draft_len) return BASS_ERR_INVALID_ARG;
+  const LaunchShape ls = launch_shape(d, K_new != nullptr);
+  rc = check_attention_args(d, ls, Q, K_new, V_new, Kcache, Vcache, O, workspace);
+  if (rc != BASS_OK) return rc;
+  const Workspace wl = workspace_layout(d, kMaxWaves);
+  if (workspace_bytes < wl.bytes) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  void* plan = (char*)workspace + wl.plan;
+  rc = launch_plan(d, ls, span, ctx_len, draft_len, plan, dev_status, stream, nullptr);
+  if (rc != BASS_OK) return rc;
+  return launch_attention(d, ls, Q, K_new, V_new, Kcache, Vcache, plan, O, lse, wl, workspace, dev_status, stream);
+}
+
 }  // namespace bass
 
 extern "C" int bass_verify_attention(const bass_attn_desc* d, const void* Q, const void* Kcache, const void* Vcache,
                                      const int32_t* ctx_len, const int32_t* draft_len, float* O, float* lse,
                                      void* workspace, size_t workspace_bytes, int32_t* dev_status, void* stream) {
-  return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
-                                workspace_bytes, dev_status, stream);
+  return bass::plan_and_launch(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                               workspace_bytes, dev_status, stream);
 }
 
 extern "C" int bass_verify_attention_pad(const bass_attn_desc* d, const void* Q, const void* Kcache,
@@ -1768,8 +1582,8 @@ extern "C" int bass_verify_attention_pad(const bass_attn_desc* d, const void* Q,
                                          int32_t padded_len, float* O, float* lse, void* workspace,
                                          size_t workspace_bytes, int32_t* dev_status, void* stream) {
   if (padded_len < 0) return BASS_ERR_INVALID_ARG;
-  return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
-                                workspace_bytes, dev_status, stream, padded_len);
+  return bass::plan_and_launch(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                               workspace_bytes, dev_status, stream, padded_len);
 }
 
 extern "C" int bass_verify_attention_split(const bass_attn_desc* d, const void* Q, const void* Kcache,
@@ -1779,18 +1593,18 @@ extern "C" int bass_verify_attention_split(const bass_attn_desc* d, const void* 
   const int rc = bass::check_desc(d);
   if (rc != BASS_OK) return rc;
   if (!Q || !Kcache || !Vcache || !ctx_len || !draft_len || !O || !workspace) return BASS_ERR_INVALID_ARG;
-  if (workspace_bytes < bass::workspace_bytes(d)) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < bass::workspace_layout(d, bass::kMaxWaves).bytes) return BASS_ERR_WORKSPACE_TOO_SMALL;
   bass_attn_desc one = *d;
   one.B = 1;
   const size_t elt = d->dtype == BASS_DTYPE_FP32 ? 4 : 2;  // Q is bf16 with bf16 and with INT8 caches
   const size_t q_seq = (size_t)d->kmax * d->Hq * d->D;  // elements of Q (and O) per sequence
   const size_t cache_seq = bass_kv_cache_bytes(&one);
-  for (int b = 0; b < d->B; ++b) {  // one launch per sequence; they share the workspace in stream order
-    const int r = bass::launch_attention(&one, (const char*)Q + b * q_seq * elt, nullptr, nullptr,
-                                         (const char*)Kcache + b * cache_seq, (const char*)Vcache + b * cache_seq,
-                                         ctx_len + b, draft_len + b, O + b * q_seq,
-                                         lse ? lse + (size_t)b * d->kmax * d->Hq : nullptr, workspace, workspace_bytes,
-                                         dev_status, stream);
+  for (int b = 0; b < d->B; ++b) {  // one plan and one launch per sequence; they share the workspace in stream order
+    const int r = bass::plan_and_launch(&one, (const char*)Q + b * q_seq * elt, nullptr, nullptr,
+                                        (const char*)Kcache + b * cache_seq, (const char*)Vcache + b * cache_seq,
+                                        ctx_len + b, draft_len + b, O + b * q_seq,
+                                        lse ? lse + (size_t)b * d->kmax * d->Hq : nullptr, workspace, workspace_bytes,
+                                        dev_status, stream);
     if (r != BASS_OK) return r;
   }
   return BASS_OK;
@@ -1805,9 +1619,36 @@ extern "C" int bass_append_verify_attention(const bass_attn_desc* d, const void*
     // more new rows than a wavefront stages in LDS: append with a launch of its own
     const int rc = bass_kv_append(d, Kcache, Vcache, K_new, V_new, ctx_len, draft_len, dev_status, stream);
     if (rc != BASS_OK) return rc;
-    return bass::launch_attention(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
-                                  workspace_bytes, dev_status, stream);
+    return bass::plan_and_launch(d, Q, nullptr, nullptr, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                                 workspace_bytes, dev_status, stream);
   }
-  return bass::launch_attention(d, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
-                                workspace_bytes, dev_status, stream);
+  return bass::plan_and_launch(d, Q, K_new, V_new, Kcache, Vcache, ctx_len, draft_len, O, lse, workspace,
+                               workspace_bytes, dev_status, stream);
+}
+
+// A verification step's attention with a plan made once for all of its layers (bass_attention_plan).
+extern "C" int bass_verify_attention_planned(const bass_attn_desc* d, const void* Q, const void* K_new, const void* V_new,
+                                             void* Kcache, void* Vcache, const void* plan, float* O, float* lse,
+                                             void* workspace, size_t workspace_bytes, int32_t* dev_status,
+                                             void* stream) {
+  int rc = bass::check_desc(d);
+  if (rc != BASS_OK) return rc;
+  if (!plan || ((uintptr_t)plan & 15) != 0) return BASS_ERR_INVALID_ARG;
+  const bass::LaunchShape ls = bass::launch_shape(d, K_new != nullptr);
+  rc = bass::check_attention_args(d, ls, Q, K_new, V_new, Kcache, Vcache, O, workspace);
+  if (rc != BASS_OK) return rc;
+  const bass::Workspace wl = bass::workspace_layout(d, bass::kMaxWaves);
+  if (workspace_bytes < wl.bytes) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  if (K_new && !ls.fused_append) {
+    // more new rows than a wavefront stages in LDS: append with a launch of its own, at the (clamped)
+    // lengths the plan holds
+    const bass::PlanLayout pl = bass::plan_layout(d->B, d->Hkv, ls.nshares);
+    const int32_t* L = (const int32_t*)((const char*)plan + pl.seq_L);
+    const int32_t* nq = (const int32_t*)((const char*)plan + pl.seq_nq);
+    rc = bass_kv_append(d, Kcache, Vcache, K_new, V_new, L, nq, dev_status, stream);
+    if (rc != BASS_OK) return rc;
+    return bass::launch_attention(d, ls, Q, nullptr, nullptr, Kcache, Vcache, plan, O, lse, wl, workspace, dev_status,
+                                  stream);
+  }
+  return bass::launch_attention(d, ls, Q, K_new, V_new, Kcache, Vcache, plan, O, lse, wl, workspace, dev_status, stream);
 }

@@ -236,3 +236,40 @@ def test_one_unit_merged_from_dozens_of_partials(hip, ctx, fused):
     # eighth with full and with ragged last rounds (48, 49 and 10 contributors)
     w = wl.make_attention("one_unit", 1, 1, 1, 128, "bf16", [ctx], [3], ctx, kmax=3, Lcap=ctx + 40)
     check_against_oracle(hip, w, waves=256, fused=fused)
+
+
+@pytest.mark.parametrize("dtype,tol", [("bf16", 5e-3), ("fp32", 1e-5)])
+@pytest.mark.parametrize("waves", [768, 8192])
+def test_alternating_inputs_on_one_workspace(hip, dtype, tol, waves):
+    # The merging wavefront must see the partial results of THIS launch: a contributor's arrival may be counted
+    # only after its partial stores have landed.  Two different batches alternate on the same caches' worth of
+    # workspace, with short contexts spread over many wavefronts (every unit has several contributors), so that
+    # a stale partial -- the other batch's values, left in the same slot by the previous launch -- would be an
+    # error of the order of the outputs themselves, far above the bar used here (tighter than the contractual
+    # one: at these short contexts |O| is 0.1 - 1).
+    import torch
+    import paper_2404_15778_amd as bass
+    D = 128 if dtype == "bf16" else 64
+    lens, nq = [400, 90, 257, 33, 480, 150], [4, 1, 3, 4, 2, 4]
+    batches = [wl.make_attention(f"alt{s}", 6, 4, 4, D, dtype, lens, nq, 100 + s, kmax=4, Lcap=512) for s in (0, 1)]
+    refs = [oracle.verify_attention(w.Q, w.K, w.V, w.ctx_len, w.draft_len, w.scale) for w in batches]
+    das, Qs = [], []
+    for w in batches:
+        _, _, _, da = hip.run_attention_workload(w, poison=True)
+        das.append(da)
+        Qs.append(hip.to_device(w.Q))
+    ctx, n = hip.i32(lens), hip.i32(nq)
+    shared = das[0].ws  # both batches' launches use this one workspace
+    bass.bass_set_attention_waves(waves)
+    try:
+        for it in range(12):
+            k = it % 2
+            da = das[k]
+            da.O.fill_(float("nan"))
+            bass.bass_verify_attention(da.desc, Qs[k], da.Kc, da.Vc, ctx, n, da.O, da.lse, shared, da.status)
+            torch.cuda.synchronize()
+            assert np.abs(hip.to_host(da.O) - refs[k][0]).max() <= tol, (it, k)
+            assert np.abs(hip.to_host(da.lse) - refs[k][1]).max() <= tol, (it, k)
+    finally:
+        bass.bass_set_attention_waves(0)
+    assert int(das[0].status.item()) == 0 and int(das[1].status.item()) == 0
