@@ -304,6 +304,24 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
 int bass_set_attention_waves(int waves);
 
 /*
+ * bass_verify_attention for callers that cannot allocate device memory or keep a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments and results as in
+ * bass_verify_attention, without the workspace: the arrival counters, the plan and the partial results
+ * live in a static device array of BASS_NOALLOC_SCRATCH_BYTES = 16 MiB inside the library (held
+ * by every GPU the library runs on until the process ends).  The call allocates nothing and frees nothing.
+ * Shapes whose scratch need -- 256-byte padded B*Hkv counters + the plan + (shares + B*Hkv) * kmax*(Hq/Hkv)
+ * * (D+2) * 4 bytes of partial results, shares being the work spread in effect -- exceeds the array are
+ * refused with BASS_ERR_WORKSPACE_TOO_SMALL before anything is enqueued (the benchmark configurations need
+ * 3.5 to 10 MiB).  All calls on one GPU share that GPU's array, which keeps the last call's contents (every
+ * call clears what must start at zero): calls that overlap in time on one GPU -- different streams,
+ * different host threads -- race and must not be made; calls on one stream are ordered and safe.
+ */
+#define BASS_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+int bass_verify_attention_noalloc(const bass_attn_desc* desc, const void* Q, const void* Kcache,
+                                  const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                                  float* O, float* lse, int32_t* dev_status, void* stream);
+
+/*
  * Measurement aid (not part of the verification step): a plain streaming read of the first
  * floor(bytes_each / 8192) * 8192 bytes of K and of V with the access pattern of the attention kernel
  * (`waves` wavefronts, each a contiguous share of 8 KiB K blocks and 8 KiB V blocks, 1 KiB per

@@ -27,7 +27,7 @@ EXPORTS = (
     "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept", "bass_warp_probs",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
     "bass_attention_plan_bytes", "bass_attention_plan", "bass_attention_plan_host", "bass_verify_attention_planned",
-    "bass_bench_stream_read",
+    "bass_bench_stream_read", "bass_verify_attention_noalloc",
 )
 
 
@@ -103,6 +103,8 @@ def lib():
         L.bass_attention_plan.argtypes = [dp, vp, vp, i32, i32, vp, sz, vp, vp]
         L.bass_attention_plan_host.restype = ctypes.c_int
         L.bass_attention_plan_host.argtypes = [dp, vp, vp, i32, i32, vp, sz, vp]
+        L.bass_verify_attention_noalloc.restype = ctypes.c_int
+        L.bass_verify_attention_noalloc.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_bench_stream_read.restype = ctypes.c_int64
         L.bass_bench_stream_read.argtypes = [vp, vp, sz, i32, vp, vp]
         L.bass_verify_attention_planned.restype = ctypes.c_int
@@ -297,6 +299,18 @@ def bass_append_verify_attention(desc, Q, K_new, V_new, Kcache, Vcache, ctx_len,
         _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
         ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
         _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_append_verify_attention")
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20  # BASS_NOALLOC_SCRATCH_BYTES of include/bass.h
+
+
+def bass_verify_attention_noalloc(desc, Q, Kcache, Vcache, ctx_len, draft_len, O, lse, dev_status=None, stream=None):
+    torch = _torch()
+    qshape = (desc.B, desc.kmax, desc.Hq, desc.D)
+    _check(lib().bass_verify_attention_noalloc(
+        *_verify_args(desc, Q, Kcache, Vcache, ctx_len, draft_len),
+        _dev(O, "O", torch.float32, qshape), _dev(lse, "lse", torch.float32, qshape[:3], optional=True),
+        _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)), "bass_verify_attention_noalloc")
 
 
 def bass_attention_plan_bytes(desc: AttnDesc) -> int:

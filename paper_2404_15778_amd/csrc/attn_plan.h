@@ -109,8 +109,9 @@ struct ShareRecord {
   int32_t nseg;       // segments of this share
   int32_t overflow;   // index of segment 2 in the overflow list (segments 2 .. nseg-1 are consecutive there)
   int32_t signature;  // plan_signature() of the plan: what a launch checks before it trusts the record
-  int32_t reserved;
+  int32_t flags;      // kRecAnyInactive (the same in every record)
 };
+constexpr int32_t kRecAnyInactive = 1;  // some sequence has no query token: its output rows still have to be cleared
 
 // What a launch and its plan must agree on, folded into one word that every record carries (a launch then
 // needs no second read to know that the record was made for it).  Never 0: cleared memory does not match.

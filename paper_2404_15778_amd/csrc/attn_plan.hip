@@ -145,6 +145,7 @@ __global__ __launch_bounds__(kPlanThreads) void attention_plan_kernel(PlanShape 
     records[w].nseg = wr.n;
     records[w].overflow = wr.n > 2 ? at : 0;
     records[w].signature = signature;
+    records[w].flags = any_inactive ? kRecAnyInactive : 0;
     at += imax(0, wr.n - 2);
   }
 
@@ -171,19 +172,19 @@ static bool plan_on_host(const PlanShape& s, int flags, const int32_t* ctx_len, 
   ShareRecord* records = (ShareRecord*)(plan + lay.records);
   Segment* overflow = (Segment*)(plan + lay.overflow);
   int32_t* owners = (int32_t*)(plan + lay.unit_owners);
-  bool bad = false, inactive = false;
+  bool bad = false, any_inactive = false;
   int carry = 0;
   for (int b = 0; b < s.B; ++b) {
     int L = ctx_len[b], nq = draft_len[b];
     bad |= clamp_lengths(L, nq, s.kmax, s.Lcap);
-    inactive |= nq == 0;
+    any_inactive |= nq == 0;
     carry += padded_blocks(s.pad, seq_blocks(s, L, nq));
     seq_L[b] = L;
     seq_nq[b] = nq;
     inc[b] = carry;
   }
   const int total = carry * s.Hkv;
-  *(PlanHeader*)plan = make_header(s, flags, total, inactive, bad);
+  *(PlanHeader*)plan = make_header(s, flags, total, any_inactive, bad);
   const int32_t signature = plan_signature(s.B, s.kmax, s.Hkv, s.Lcap, s.nshares, flags);
   int at = 0;
   for (int w = 0; w < s.nshares; ++w) {
@@ -193,6 +194,7 @@ static bool plan_on_host(const PlanShape& s, int flags, const int32_t* ctx_len, 
     records[w].nseg = wr.n;
     records[w].overflow = wr.n > 2 ? at : 0;
     records[w].signature = signature;
+    records[w].flags = any_inactive ? kRecAnyInactive : 0;
     at += imax(0, wr.n - 2);
   }
   const Split sp = make_split(total, s.nshares);

@@ -32,6 +32,7 @@
 // Query rows of one kv head are (draft i, head-in-group) pairs, up to 64 rows = 4 tiles.
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "bass_common.h"
@@ -169,9 +170,9 @@ __device__ inline float2 load_dev(const float* src) {
 // DC: the head size when it is known at compile time (the divisions below then cost nothing; this code
 // runs before a wavefront's first K/V load), 0: read it from the descriptor.
 template <int DC>
-__device__ inline void zero_rows(const AttnParams& p, int b, int kvh, int row_from, int lane) {
+__device__ inline void zero_rows(const AttnParams& p, int b, int kvh, int row_from, int lane, int row_to = 1 << 30) {
   const int D = DC ? DC : p.D, lpr = D / 4, rpi = 64 / lpr;
-  const int rows_all = p.kmax * p.g;
+  const int rows_all = min(p.kmax * p.g, row_to);
   for (int r0 = row_from; r0 < rows_all; r0 += rpi) {
     const int r = r0 + lane / lpr;
     if (lane < rpi * lpr && r < rows_all) {
@@ -419,7 +420,6 @@ __device__ inline void arrive(const AttnParams& p, int lane, CombineJob& ja, boo
 // one-tile matrix-core kernel: by the wavefront that holds the unit's last block).
 template <int DC, bool kInactiveOnly = false>
 __device__ inline void zero_unused_rows(const AttnParams& p, int w, int nw, int lane) {
-  if (kInactiveOnly && !p.plan->any_inactive) return;
   for (int unit = w; unit < p.B * p.Hkv; unit += nw) {
     const int b = unit / p.Hkv;
     const int nq = uniform(p.seq_nq[b]);
@@ -964,6 +964,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   Segment sa = load_segment(&rec->seg[0]);
   Segment sb = load_segment(&rec->seg[1]);
   int nseg_plan = uniform(rec->nseg), overflow = uniform(rec->overflow);
+  const int rec_flags = uniform(rec->flags);
   __builtin_amdgcn_sched_barrier(0);  // the loads above are issued here, whatever is scheduled below
   bool ok;
   int nseg;
@@ -1148,7 +1149,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   // Unused query rows of inactive sequences (those of an active one are cleared by the wavefront that
   // holds the unit's last block, right before its partial stores: that wavefront is handed fewer real
   // blocks, and the stores are acknowledged together with the partials)
-  zero_unused_rows<D, true>(p, w, p.nwaves, lane);
+  if (rec_flags & kRecAnyInactive) zero_unused_rows<D, true>(p, w, p.nwaves, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1183,7 +1184,7 @@ __global__ __launch_bounds__(256, 2) void verify_attn_tiles_bf16(AttnParams p) {
     report_mismatch(p, wg == 0 && threadIdx.x == 0);
     return;
   }
-  zero_unused_rows<D>(p, wg * 4 + wv, 4 * p.nshares, lane);
+  // (the unused query rows are cleared by the merge launch, which visits every row of every unit anyway)
 
   const uint4* kc = (const uint4*)p.Kc;
   const uint4* vc = (const uint4*)p.Vc;
@@ -1298,6 +1299,8 @@ __global__ __launch_bounds__(256) void reduce_partials(AttnParams p) {
   const int b = unit / p.Hkv, kvh = unit % p.Hkv;
   if (!record_matches(p, p.records)) return;  // reported by the attention launch
   const int nq = uniform(p.seq_nq[b]);
+  // query slots beyond draft_len (all of them for an inactive sequence) are zero in O and lse
+  if (4 * sweep + 4 > nq * p.g) zero_rows<DC>(p, b, kvh, max(nq * p.g, 4 * sweep), lane, 4 * sweep + 4);
   if (nq == 0 || 4 * sweep >= nq * p.g) return;
   const int owners = uniform(p.unit_owners[unit]);
   CombineJob job{Unit{b, kvh, uniform(p.seq_L[b]), nq}, owners & 0xFFFF, (owners >> 16) & 0xFFFF};
@@ -1651,4 +1654,56 @@ extern "C" int bass_verify_attention_planned(const bass_attn_desc* d, const void
                                   stream);
   }
   return bass::launch_attention(d, ls, Q, K_new, V_new, Kcache, Vcache, plan, O, lse, wl, workspace, dev_status, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// bass_verify_attention_noalloc: for callers that cannot allocate or own a workspace.  The arrival
+// counters, the plan and the partial results live in a file-scope device array.  In host code the array's
+// name is only a stand-in: its device address is asked for once per device (hipGetSymbolAddress, with that
+// device current) and that pointer, never the name, is what launches receive.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kScratchBytes = BASS_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace bass {
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];  // per device: each GPU holds its own copy of the array
+static std::mutex g_scratch_mutex;
+
+static int scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BASS_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return BASS_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BASS_OK;
+}
+
+}  // namespace bass
+
+extern "C" int bass_verify_attention_noalloc(const bass_attn_desc* d, const void* Q, const void* Kcache,
+                                             const void* Vcache, const int32_t* ctx_len, const int32_t* draft_len,
+                                             float* O, float* lse, int32_t* dev_status, void* stream) {
+  int rc = bass::check_desc(d);
+  if (rc != BASS_OK) return rc;
+  if (!ctx_len || !draft_len) return BASS_ERR_INVALID_ARG;
+  const bass::LaunchShape ls = bass::launch_shape(d, false);
+  // laid out for the shares this launch really uses, not for the largest spread the tuning knob allows
+  const bass::Workspace wl = bass::workspace_layout(d, ls.nshares);
+  if (wl.bytes > kScratchBytes) return BASS_ERR_WORKSPACE_TOO_SMALL;
+  void* ptr = nullptr;
+  rc = bass::scratch_address(&ptr);
+  if (rc != BASS_OK) return rc;
+  rc = bass::check_attention_args(d, ls, Q, nullptr, nullptr, Kcache, Vcache, O, ptr);
+  if (rc != BASS_OK) return rc;
+  void* plan = (char*)ptr + wl.plan;
+  // the array keeps the last call's contents: the planning launch also clears the arrival counters
+  rc = bass::launch_plan(d, ls, 0, ctx_len, draft_len, plan, dev_status, stream, (int32_t*)ptr);
+  if (rc != BASS_OK) return rc;
+  return bass::launch_attention(d, ls, Q, nullptr, nullptr, Kcache, Vcache, plan, O, lse, wl, ptr, dev_status, stream);
 }

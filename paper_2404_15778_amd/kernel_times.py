@@ -1,14 +1,15 @@
 """Calls of the library on the synthetic configurations, for timing under a profiler.
 
     python -m paper_2404_15778_amd.kernel_times attention --cfg 2 [--dtype bf16|int8kv] [--waves 0,1024]
-                                                           [--slabs 16] [--fused] [--reps 3]
+                                                           [--slabs 16] [--fused] [--planned] [--reps 3]
     python -m paper_2404_15778_amd.kernel_times logits [--reps 5] [--temperature T --top-p P]
     python -m paper_2404_15778_amd.kernel_times summarize <kernel_trace.csv>
 
 `attention` fills --slabs cache slabs of one attention configuration (workloads.config2/3/4, seed 0) with
 bass_kv_append, so that consecutive calls cannot be served by the last-level cache, and calls
-bass_verify_attention (or, with --fused, bass_append_verify_attention) over them --reps times per
-wavefront setting (0 = the library's default).  It prints the time per call seen by HIP events, which
+bass_verify_attention (or, with --fused, bass_append_verify_attention; with --planned, one
+bass_attention_plan per sweep over the slabs and bass_verify_attention_planned per slab, as a verification
+step does) over them --reps times per wavefront setting (0 = the library's default).  It prints the time per call seen by HIP events, which
 includes the hand-over between launches; kernel durations come from running the same command under
 `rocprofv3 --kernel-trace --output-format csv -d <dir> -o <name> -- python3 <repo>/paper_2404_15778_amd/kernel_times.py attention ...`
 and passing `<dir>/<name>_kernel_trace.csv` to `summarize` (average, median and minimum of End - Start per
@@ -62,15 +63,21 @@ def attention(args):
     ws = bass.alloc_workspace(desc, dev)
     O = torch.empty((w.B, w.kmax, w.Hq, w.D), dtype=torch.float32, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
+    plan = bass.alloc_plan(desc, dev)
     print(f"cfg{args.cfg} {args.dtype}: kv_bytes (bf16-equivalent) {w.kv_bytes}", flush=True)
     try:
         for waves in args.waves:
             in_effect = bass.bass_set_attention_waves(waves)
             for _ in range(args.reps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                if args.planned:
+                    bass.bass_attention_plan(desc, ctx, nq, bass.PLAN_APPEND if args.fused else 0, 0, plan, status)
                 e0.record()
                 for Kc, Vc in slabs:
-                    if args.fused:
+                    if args.planned:
+                        bass.bass_verify_attention_planned(desc, Q, Kn if args.fused else None, Vn if args.fused else None,
+                                                           Kc, Vc, plan, O, None, ws, status)
+                    elif args.fused:
                         bass.bass_append_verify_attention(desc, Q, Kn, Vn, Kc, Vc, ctx, nq, O, None, ws, status)
                     else:
                         bass.bass_verify_attention(desc, Q, Kc, Vc, ctx, nq, O, None, ws, status)
@@ -136,6 +143,7 @@ def main():
     a.add_argument("--slabs", type=int, default=16)
     a.add_argument("--reps", type=int, default=3)
     a.add_argument("--fused", action="store_true")
+    a.add_argument("--planned", action="store_true")
     a.set_defaults(run=attention)
     g = sub.add_parser("logits")
     g.add_argument("--reps", type=int, default=5)
