@@ -16,6 +16,10 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 VALU ops are kept off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-core results stay in ordinary vector registers where they fit: the kernels run one wavefront per
+    # SIMD, every instruction is paid for, and the copies to and from accumulator registers were a quarter of
+    # the attention kernel's streaming loop
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wno-unused-command-line-argument",
 ]
 

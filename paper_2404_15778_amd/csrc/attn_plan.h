@@ -45,7 +45,8 @@ BASS_HD inline bool clamp_lengths(int& L, int& nq, int kmax, int Lcap) {
 // What the division depends on besides the lengths.
 struct PlanShape {
   int32_t B, kmax, Hkv, Lcap;
-  int32_t nshares;     // stretches the block list is cut into
+  int32_t nshares;     // stretches the launch has room for (one record each)
+  int32_t target;      // stretches aimed at (<= nshares); see plan_split
   int32_t pad;         // virtual blocks of every unit in the flattened list
   int32_t pad_before;  // how many of them sit in front of the unit's last real block
   int32_t span;        // BASS-PAD variant: every active sequence is processed over at least this many cache
@@ -74,16 +75,30 @@ BASS_HD inline int real_below(int t, int nblk, int pb) {  // real blocks at entr
 }
 BASS_HD inline int entry_of(int j, int nblk, int pb) { return j < nblk - 1 ? j : j + pb; }  // entry of real block j
 
-// Even division of the flattened list: shares 0 .. rem-1 take per + 1 consecutive entries, the others per.
+// Division of the flattened list into consecutive stretches: shares 0 .. rem-1 take per + 1 entries, the
+// following ones per, until the list ends (shares beyond that are empty).
 struct Split {
-  int per, rem;
-  BASS_HD int first(int w) const { return w * per + imin(w, rem); }  // first entry of share w
-  BASS_HD int owner(int x) const {                                   // share that holds entry x
+  int per, rem, total;
+  BASS_HD int first(int w) const { return imin(w * per + imin(w, rem), total); }  // first entry of share w
+  BASS_HD int owner(int x) const {                                                // share that holds entry x
     const int big = rem * (per + 1);
     return x < big ? x / (per + 1) : rem + (x - big) / imax(per, 1);
   }
 };
-BASS_HD inline Split make_split(int total, int nshares) { return Split{total / nshares, total % nshares}; }
+// Even division over exactly n shares: they differ by at most one entry.
+BASS_HD inline Split make_split(int total, int n) { return Split{total / n, total % n, total}; }
+
+// The division a plan uses.  A launch lasts as long as its longest share, and with an even division over
+// `target` shares most of them are one entry longer than total / target.  If the launch has room for more
+// shares than it aims at (nshares > target), all shares get floor(total / target) entries instead and there
+// are correspondingly more of them (at most nshares: the share length grows until they fit); the last one
+// takes what is left, the launch's remaining wavefronts stay idle.
+BASS_HD inline Split plan_split(const PlanShape& s, int total) {
+  if (s.target >= s.nshares || total <= 0) return make_split(total, s.nshares);
+  int per = imax(1, total / s.target);
+  while ((total + per - 1) / per > s.nshares) ++per;
+  return Split{per, 0, total};
+}
 
 // pb in effect: the split placement is switched off when shares are not longer than a unit's pad, so that
 // no share can lie between two real blocks of a unit without holding one (every share between a unit's
@@ -107,7 +122,8 @@ BASS_HD inline int seg_w_hi(const Segment& s) { return (s.owners >> 16) & 0xFFFF
 struct ShareRecord {
   Segment seg[2];
   int32_t nseg;       // segments of this share
-  int32_t overflow;   // index of segment 2 in the overflow list (segments 2 .. nseg-1 are consecutive there)
+  int32_t overflow;   // index of segment 2 in the overflow list (segments 2 .. nseg-1 are consecutive there); it is
+                      // share + unit index of that segment, which keeps the runs of different shares apart
   int32_t signature;  // plan_signature() of the plan: what a launch checks before it trusts the record
   int32_t flags;      // kRecAnyInactive (the same in every record)
 };
@@ -180,7 +196,7 @@ template <class Emit>
 BASS_HD inline int plan_share(const PlanShape& s, const int32_t* seq_L, const int32_t* seq_nq, const int32_t* inc, int w,
                               Emit&& emit) {
   const int total = inc[s.B - 1] * s.Hkv;
-  const Split sp = make_split(total, s.nshares);
+  const Split sp = plan_split(s, total);
   const int pb = pad_before_in_effect(s, sp);
   int x = sp.first(w);
   const int x_end = sp.first(w + 1);

@@ -11,11 +11,14 @@
 
 namespace bass {
 
-// One workgroup plans a step.  Phase 1: clamp the lengths, count blocks, inclusive prefix over the
-// sequences.  Phase 2: every thread takes a run of consecutive shares, counts their segments, the
-// workgroup scans the counts (so that the overflow list is in share order, exactly as the host planner
-// writes it), and the segments are written.  Phase 3: the contributors of every unit, for the merge launch.
-constexpr int kPlanThreads = 1024;
+// Planning kernel.  Phase 1: clamp the lengths, count blocks, inclusive prefix over the sequences.  Phase 2: one
+// thread per share walks its stretch of the block list and writes the record.  Phase 3: the contributors of
+// every unit, for the merge launch.  Batches of up to kPlanSeqs sequences keep phase 1's results in LDS, every
+// workgroup computes them for itself (a few hundred instructions) and the shares are spread over several
+// workgroups, i.e. compute units: the walk is serial integer arithmetic with divisions, and one compute unit
+// needs 10 us for 768 shares.  Larger batches are planned by a single workgroup through global memory.
+constexpr int kPlanThreads = 256;
+constexpr int kPlanSeqs = 1024;
 
 // Inclusive prefix sum over the workgroup's kPlanThreads values and their total; all threads call.
 __device__ inline int block_incl_scan(int v, int* lds, int tid, int& total) {
@@ -39,24 +42,44 @@ __device__ inline int block_incl_scan(int v, int* lds, int tid, int& total) {
   return x + base;
 }
 
+// Writes the segments of share w: the first two into its record, the others into the overflow list from entry
+// w + (unit of the third segment) on.  These runs cannot overlap: the units of a share are distinct and
+// increasing, and the next share starts at a unit that is not smaller than this share's last one.
 struct RecordWriter {
   ShareRecord* rec;
   Segment* overflow;
-  int n;
+  int w, Hkv, n, base;
   BASS_HD void operator()(const Segment& g) {
-    if (n < 2) rec->seg[n] = g;
-    else overflow[n - 2] = g;
+    if (n < 2) {
+      rec->seg[n] = g;
+    } else {
+      if (n == 2) base = w + g.b * Hkv + g.kvh;
+      overflow[base + n - 2] = g;
+    }
     ++n;
   }
-};
-
-struct Counter {
-  BASS_HD void operator()(const Segment&) {}
 };
 
 BASS_HD inline void clear_record(ShareRecord* r) {
   int32_t* w = (int32_t*)r;
   for (size_t i = 0; i < sizeof(ShareRecord) / 4; ++i) w[i] = 0;
+}
+
+BASS_HD inline void write_record(const PlanShape& s, const int32_t* seq_L, const int32_t* seq_nq, const int32_t* inc, int total,
+                                 int w, int32_t signature, bool any_inactive, ShareRecord* records, Segment* overflow) {
+  clear_record(&records[w]);
+  RecordWriter wr{&records[w], overflow, w, s.Hkv, 0, 0};
+  if (total > 0) plan_share(s, seq_L, seq_nq, inc, w, wr);
+  records[w].nseg = wr.n;
+  records[w].overflow = wr.base;
+  records[w].signature = signature;
+  records[w].flags = any_inactive ? kRecAnyInactive : 0;
+}
+
+BASS_HD inline int32_t owners_of_unit(const PlanShape& s, const Split& sp, int pb, const int32_t* inc, int unit) {
+  const int b = unit / s.Hkv, kvh = unit - b * s.Hkv;
+  const int npad = inc[b] - (b > 0 ? inc[b - 1] : 0);
+  return npad > 0 ? unit_owners(sp, (inc[b] - npad) * s.Hkv + kvh * npad, npad - s.pad, pb) : 0;
 }
 
 BASS_HD inline PlanHeader make_header(const PlanShape& s, int flags, int total, bool any_inactive, bool any_clamped) {
@@ -78,9 +101,11 @@ __global__ __launch_bounds__(kPlanThreads) void attention_plan_kernel(PlanShape 
                                                                       const int32_t* draft_len, char* plan, int32_t* status,
                                                                       int32_t* clear_counters) {
   __shared__ int lds[kPlanThreads / 64];
-  // lengths and prefix of batches of up to kPlanThreads sequences also stay in LDS for the searches of phase 2
-  __shared__ int32_t lds_L[kPlanThreads], lds_nq[kPlanThreads], lds_inc[kPlanThreads];
+  __shared__ int32_t lds_L[kPlanSeqs], lds_nq[kPlanSeqs], lds_inc[kPlanSeqs];
   const int tid = threadIdx.x;
+  const int gtid = blockIdx.x * kPlanThreads + tid, gthreads = gridDim.x * kPlanThreads;
+  const bool first = blockIdx.x == 0;
+  const bool in_lds = s.B <= kPlanSeqs;  // else: one workgroup (the host launches it so), results through global memory
   const PlanLayout lay = plan_layout(s.B, s.Hkv, s.nshares);
   int32_t* seq_L = (int32_t*)(plan + lay.seq_L);
   int32_t* seq_nq = (int32_t*)(plan + lay.seq_nq);
@@ -90,9 +115,9 @@ __global__ __launch_bounds__(kPlanThreads) void attention_plan_kernel(PlanShape 
   int32_t* owners = (int32_t*)(plan + lay.unit_owners);
 
   if (clear_counters)
-    for (int i = tid; i < s.B * s.Hkv; i += kPlanThreads) clear_counters[i] = 0;
+    for (int i = gtid; i < s.B * s.Hkv; i += gthreads) clear_counters[i] = 0;
 
-  // phase 1
+  // phase 1 (every workgroup for itself; the first one also writes the plan's copy)
   int carry = 0;
   bool bad = false, inactive = false;
   for (int c0 = 0; c0 < s.B; c0 += kPlanThreads) {
@@ -104,63 +129,43 @@ __global__ __launch_bounds__(kPlanThreads) void attention_plan_kernel(PlanShape 
       bad |= clamp_lengths(L, nq, s.kmax, s.Lcap);
       inactive |= nq == 0;
       nb = padded_blocks(s.pad, seq_blocks(s, L, nq));
-      seq_L[b] = L;
-      seq_nq[b] = nq;
     }
     int chunk_total;
-    const int incl = block_incl_scan(nb, lds, tid, chunk_total);
-    if (b < s.B) inc[b] = carry + incl;
-    if (c0 == 0) {
-      lds_L[tid] = L;
-      lds_nq[tid] = nq;
-      lds_inc[tid] = incl;
+    const int incl = carry + block_incl_scan(nb, lds, tid, chunk_total);
+    if (b < s.B) {
+      if (first) {
+        seq_L[b] = L;
+        seq_nq[b] = nq;
+        inc[b] = incl;
+      }
+      if (in_lds) {
+        lds_L[b] = L;
+        lds_nq[b] = nq;
+        lds_inc[b] = incl;
+      }
     }
     carry += chunk_total;
   }
   const int any_bad = __syncthreads_or(bad ? 1 : 0);
   const int any_inactive = __syncthreads_or(inactive ? 1 : 0);  // also orders the writes above before the reads below
   const int total = carry * s.Hkv;
-  if (tid == 0) {
+  if (first && tid == 0) {
     *(PlanHeader*)plan = make_header(s, flags, total, any_inactive != 0, any_bad != 0);
     if (any_bad && status) atomicOr(status, BASS_STATUS_LEN_CLAMPED);
   }
-  const bool in_lds = s.B <= kPlanThreads;
   const int32_t* rd_L = in_lds ? lds_L : seq_L;
   const int32_t* rd_nq = in_lds ? lds_nq : seq_nq;
   const int32_t* rd_inc = in_lds ? lds_inc : inc;
 
   // phase 2
   const int32_t signature = plan_signature(s.B, s.kmax, s.Hkv, s.Lcap, s.nshares, flags);
-  const int per_thread = (s.nshares + kPlanThreads - 1) / kPlanThreads;
-  const int w0 = tid * per_thread, w1 = imin(s.nshares, w0 + per_thread);
-  int extra = 0;  // segments of my shares that go to the overflow list
-  if (total > 0)
-    for (int w = w0; w < w1; ++w) extra += imax(0, plan_share(s, rd_L, rd_nq, rd_inc, w, Counter{}) - 2);
-  int extra_total;
-  int at = block_incl_scan(extra, lds, tid, extra_total) - extra;
-  for (int w = w0; w < w1; ++w) {
-    clear_record(&records[w]);
-    RecordWriter wr{&records[w], overflow + at, 0};
-    if (total > 0) plan_share(s, rd_L, rd_nq, rd_inc, w, wr);
-    records[w].nseg = wr.n;
-    records[w].overflow = wr.n > 2 ? at : 0;
-    records[w].signature = signature;
-    records[w].flags = any_inactive ? kRecAnyInactive : 0;
-    at += imax(0, wr.n - 2);
-  }
+  for (int w = gtid; w < s.nshares; w += gthreads)
+    write_record(s, rd_L, rd_nq, rd_inc, total, w, signature, any_inactive != 0, records, overflow);
 
   // phase 3
-  if (total > 0) {
-    const Split sp = make_split(total, s.nshares);
-    const int pb = pad_before_in_effect(s, sp);
-    for (int unit = tid; unit < s.B * s.Hkv; unit += kPlanThreads) {
-      const int b = unit / s.Hkv, kvh = unit - b * s.Hkv;
-      const int npad = rd_inc[b] - (b > 0 ? rd_inc[b - 1] : 0);
-      owners[unit] = npad > 0 ? unit_owners(sp, (rd_inc[b] - npad) * s.Hkv + kvh * npad, npad - s.pad, pb) : 0;
-    }
-  } else {
-    for (int unit = tid; unit < s.B * s.Hkv; unit += kPlanThreads) owners[unit] = 0;
-  }
+  const Split sp = plan_split(s, total);
+  const int pb = pad_before_in_effect(s, sp);
+  for (int unit = gtid; unit < s.B * s.Hkv; unit += gthreads) owners[unit] = total > 0 ? owners_of_unit(s, sp, pb, rd_inc, unit) : 0;
 }
 
 // The same plan, byte for byte, written by the host into host memory.
@@ -186,31 +191,17 @@ static bool plan_on_host(const PlanShape& s, int flags, const int32_t* ctx_len, 
   const int total = carry * s.Hkv;
   *(PlanHeader*)plan = make_header(s, flags, total, any_inactive, bad);
   const int32_t signature = plan_signature(s.B, s.kmax, s.Hkv, s.Lcap, s.nshares, flags);
-  int at = 0;
-  for (int w = 0; w < s.nshares; ++w) {
-    clear_record(&records[w]);
-    RecordWriter wr{&records[w], overflow + at, 0};
-    if (total > 0) plan_share(s, seq_L, seq_nq, inc, w, wr);
-    records[w].nseg = wr.n;
-    records[w].overflow = wr.n > 2 ? at : 0;
-    records[w].signature = signature;
-    records[w].flags = any_inactive ? kRecAnyInactive : 0;
-    at += imax(0, wr.n - 2);
-  }
-  const Split sp = make_split(total, s.nshares);
+  for (int w = 0; w < s.nshares; ++w) write_record(s, seq_L, seq_nq, inc, total, w, signature, any_inactive, records, overflow);
+  const Split sp = plan_split(s, total);
   const int pb = pad_before_in_effect(s, sp);
-  for (int unit = 0; unit < s.B * s.Hkv; ++unit) {
-    const int b = unit / s.Hkv, kvh = unit - b * s.Hkv;
-    const int npad = inc[b] - (b > 0 ? inc[b - 1] : 0);
-    owners[unit] = (total > 0 && npad > 0) ? unit_owners(sp, (inc[b] - npad) * s.Hkv + kvh * npad, npad - s.pad, pb) : 0;
-  }
+  for (int unit = 0; unit < s.B * s.Hkv; ++unit) owners[unit] = total > 0 ? owners_of_unit(s, sp, pb, inc, unit) : 0;
   return bad;
 }
 
 PlanShape plan_shape(const bass_attn_desc* d, const LaunchShape& ls, int span) {
   PlanShape s;
   s.B = d->B; s.kmax = d->kmax; s.Hkv = d->Hkv; s.Lcap = d->Lcap;
-  s.nshares = ls.nshares; s.pad = ls.pad; s.pad_before = ls.pad_before; s.span = span;
+  s.nshares = ls.nshares; s.target = ls.target; s.pad = ls.pad; s.pad_before = ls.pad_before; s.span = span;
   return s;
 }
 
@@ -219,7 +210,8 @@ size_t plan_bytes_max(const bass_attn_desc* d) { return plan_layout(d->B, d->Hkv
 int launch_plan(const bass_attn_desc* d, const LaunchShape& ls, int span, const int32_t* ctx_len, const int32_t* draft_len,
                 void* plan, int32_t* dev_status, void* stream, int32_t* clear_counters) {
   const PlanShape s = plan_shape(d, ls, span);
-  hipLaunchKernelGGL(attention_plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream, s,
+  const unsigned groups = s.B <= kPlanSeqs ? (unsigned)((s.nshares + kPlanThreads - 1) / kPlanThreads) : 1u;
+  hipLaunchKernelGGL(attention_plan_kernel, dim3(groups), dim3(kPlanThreads), 0, (hipStream_t)stream, s,
                      ls.fused_append ? kPlanAppend : 0, ctx_len, draft_len, (char*)plan, dev_status, clear_counters);
   return launch_status();
 }

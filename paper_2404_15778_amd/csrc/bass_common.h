@@ -130,7 +130,7 @@ struct LaunchShape {
   bool mfma;        // bf16 or INT8 caches: the matrix-core kernels
   bool tiles;       // bf16 caches, more than one 16-row query tile per kv head: the workgroup-level kernel
   bool fused_append;  // the step's rows are appended inside the attention launch
-  int rows_max, nwaves, nshares, pad, pad_before, fused_reduce;
+  int rows_max, nwaves, nshares, target, pad, pad_before, fused_reduce;
 };
 
 // many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
@@ -151,10 +151,14 @@ inline LaunchShape launch_shape(const bass_attn_desc* d, bool append) {
   s.mfma = d->dtype != BASS_DTYPE_FP32;
   s.tiles = d->dtype == BASS_DTYPE_BF16 && s.rows_max > 16;
   s.fused_append = append && (d->dtype == BASS_DTYPE_FP32 || (int64_t)d->kmax * d->D <= kMaxStagedElems);
-  s.nwaves = attention_waves(setting, s.mfma && s.rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
+  // (a launch wider than the shares it aims at, with all shares equally long -- plan_split -- was measured
+  // 1 - 2 % slower than the even division on the benchmark shapes: more wavefronts, more partials to merge)
+  const int aim = attention_waves(setting, s.mfma && s.rows_max > 16, d->dtype == BASS_DTYPE_INT8KV);
+  s.nwaves = aim;
   // the workgroup-level kernel takes one stretch per workgroup (default 256, measured best: fewer
   // partials to merge; a wavefront setting W gives W / 2)
   s.nshares = !s.tiles ? s.nwaves : setting > 0 ? (s.nwaves / 2 > 16 ? s.nwaves / 2 : 16) : 256;
+  s.target = !s.tiles ? aim : s.nshares;
   s.pad = s.fused_append ? kAppendPad : kPlainPad;
   s.pad_before = 0;
   if (s.mfma && s.rows_max <= 16) s.pad_before = s.fused_append ? kAppendBefore : kPlainBefore;

@@ -99,8 +99,26 @@ __device__ inline Segment load_segment(const Segment* src) {
 }
 
 // Segment si >= 1 of a share
+__device__ inline const Segment* later_segment_address(const AttnParams& p, const ShareRecord* rec, int overflow, int si) {
+  return si == 1 ? &rec->seg[1] : p.overflow + overflow + (si - 2);
+}
 __device__ inline Segment later_segment(const AttnParams& p, const ShareRecord* rec, int overflow, int si) {
-  return load_segment(si == 1 ? &rec->seg[1] : p.overflow + overflow + (si - 2));
+  return load_segment(later_segment_address(p, rec, overflow, si));
+}
+
+// A segment requested early and used late (its address is the same in every lane): the request travels while
+// the wavefront streams, so that going on to the next units of a long share costs no round trip.
+struct SegmentInFlight {
+  i32x4 a, b;
+};
+__device__ inline SegmentInFlight request_segment(const Segment* src) {
+  return SegmentInFlight{*(const i32x4*)src, *((const i32x4*)src + 1)};
+}
+__device__ inline Segment arrived_segment(const SegmentInFlight& f) {
+  Segment g;
+  g.b = uniform(f.a[0]); g.kvh = uniform(f.a[1]); g.L = uniform(f.a[2]); g.nq = uniform(f.a[3]);
+  g.first = uniform(f.b[0]); g.n = uniform(f.b[1]); g.owners = uniform(f.b[2]); g.flags = uniform(f.b[3]);
+  return g;
 }
 
 // The plan must have been made for this launch: same batch shape, same number of shares, and for a launch
@@ -661,6 +679,8 @@ __device__ inline void patch_block_i8(KvRegsI8<D>& q, int tok0, const NewRows nr
   }
 }
 
+constexpr float kMaxSlack = 8.f;  // see block_step
+
 template <int D, int NT>
 struct RowState {
   f32x4 acc[NT][D / 16];
@@ -789,11 +809,25 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
     }
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = rows4_max(mx);
-    const float m_new = fmaxf(st.m[nt], mx);
+    // The reference maximum of a row moves only when a block exceeds it by more than kMaxSlack (log2 units).
+    // The probabilities are then at most 2^kMaxSlack -- harmless in the fp32 sums and in the bf16 operand --
+    // and the rescale of the running sum and of the accumulator (a third of a block step's instructions at
+    // one wavefront per SIMD, where every instruction is paid for) runs in a unit's first block and hardly
+    // ever again.  Wave-uniform branch; a row that does not move has alpha = 1.
+    const float m_old = st.m[nt];
+    const bool grow = mx > m_old + kMaxSlack;
+    if (__any(grow)) {
+      const float m_new = grow ? mx : m_old;
+      const float m_to = (kMasked && m_new == -INFINITY) ? 0.f : m_new;  // rows without a visible token yet
+      const float alpha = __builtin_amdgcn_exp2f(m_old - m_to);
+      st.l[nt] *= alpha;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) st.acc[nt][mt] *= alpha;
+      st.m[nt] = m_new;
+    }
     // a row that has seen no visible token yet keeps m = -inf; subtract 0 instead so that
     // exp2(-inf - 0) = 0 and no inf - inf appears
-    const float m_use = (kMasked && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_use);
+    const float m_use = (kMasked && st.m[nt] == -INFINITY) ? 0.f : st.m[nt];
     float psum = 0.f;
     bf16x8 pf;
 #pragma unroll
@@ -802,11 +836,10 @@ __device__ inline void block_step(KvRegs<D>& r, const bf16x8 (&qf)[NT][D / 32], 
       psum += pj;
       pf[j] = (__bf16)(kI8 ? pj * vsl[j] : pj);
     }
-    st.l[nt] = st.l[nt] * alpha + psum;
-    st.m[nt] = m_new;
+    st.l[nt] += psum;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, st.acc[nt][mt] * alpha, 0, 0, 0);
+      st.acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.v[mt]), pf, st.acc[nt][mt], 0, 0, 0);
   }
 }
 
@@ -988,6 +1021,13 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
     const Unit uA = unit_of(sa);
     const int nA = sa.n;  // our real blocks of unit A: firstA .. firstA + nA - 1
     const bool hasB = kPair && si + 1 < nseg;
+    // the segments after these (shares that touch more units than the record holds) are requested now and
+    // looked at when this pair is done; without any, the request re-reads the record (loads stay outside
+    // branches: the wait counts of the K/V ring must stay exact)
+    const int si_next = si + (hasB ? 2 : 1);
+    const SegmentInFlight nextA = request_segment(si_next < nseg ? later_segment_address(p, rec, overflow, si_next) : &rec->seg[0]);
+    const SegmentInFlight nextB =
+        request_segment(kPair && si_next + 1 < nseg ? later_segment_address(p, rec, overflow, si_next + 1) : &rec->seg[1]);
     const Unit uB = hasB ? unit_of(sb) : uA;
     const int firstB = hasB ? sb.first : 0, nB = hasB ? sb.n : 0;
     const bool lastA = (sa.flags & kSegLast) != 0, lastB = hasB && (sb.flags & kSegLast) != 0;  // we hold the unit's last block
@@ -1096,6 +1136,13 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         block_dispatch<D, NT>(r, qc.q, st, cur_blk + s, cur_L, cur_valid, qc.lim, p.scale_log2, lane, fused, cur_new, kdst, vdst);
       }
     };
+    // Unused query rows of a unit are cleared by the wavefront that holds the unit's last block (it is handed
+    // fewer real blocks), while its first fetches are under way: the stores are acknowledged long before the
+    // wavefront waits for its partial stores at the end, and nothing waits for them here.
+    auto clear_unused = [&]() {
+      if (lastA) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
+      if (lastB) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
+    };
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
       Regs r1, r2;  // r0 is on its way already
@@ -1104,6 +1151,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         commit(u1, 0, sr, new1);  // these loads were issued before the fetches
         stage_rest();
       }
+      clear_unused();
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
@@ -1119,6 +1167,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         commit(u1, 0, sr, new1);
         stage_rest();
       }
+      clear_unused();
       for (int s = 0; s < n; s += 2) {
         fetch(r1, s + 1);
         step(r0, s);
@@ -1126,8 +1175,6 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         if (s + 1 < n) step(r1, s + 1);
       }
     }
-    if (lastA) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
-    if (lastB) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
     if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
     store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
     if (p.fused_reduce) {  // otherwise a second launch merges the partials
@@ -1136,19 +1183,15 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       arrive(p, lane, ja, mergeA, hasB, jb, mergeB);
       if (mergeA || mergeB) combine_jobs<D>(p, ja, mergeA, jb, mergeB, lane);
     }
-    si += hasB ? 2 : 1;
-    if (si < nseg) {  // shares that touch more units than the record holds
-      sa = later_segment(p, rec, overflow, si);
-      if (kPair && si + 1 < nseg) sb = later_segment(p, rec, overflow, si + 1);
-    }
+    si = si_next;
+    sa = arrived_segment(nextA);
+    sb = arrived_segment(nextB);
   } while (si < nseg);
   if (!ok) {
     report_mismatch(p, w == 0 && lane == 0);
     return;
   }
-  // Unused query rows of inactive sequences (those of an active one are cleared by the wavefront that
-  // holds the unit's last block, right before its partial stores: that wavefront is handed fewer real
-  // blocks, and the stores are acknowledged together with the partials)
+  // Unused query rows of inactive sequences (those of an active one: clear_unused above)
   if (rec_flags & kRecAnyInactive) zero_unused_rows<D, true>(p, w, p.nwaves, lane);
 }
 

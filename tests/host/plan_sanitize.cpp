@@ -39,13 +39,25 @@ static int check_case(const PlanShape& s, const std::vector<int32_t>& ctx, const
     inc[b] = carry;
   }
   const int total = carry * s.Hkv;
-  const Split sp = make_split(total, s.nshares);
+  const Split sp = plan_split(s, total);
   if (sp.first(s.nshares) != total) return fail("split does not cover the list", total);
+  int longest = 0, shortest = 1 << 30, nonempty = 0;
   for (int w = 0; w < s.nshares && total > 0; ++w) {
-    if (sp.first(w) < sp.first(w + 1) && sp.owner(sp.first(w)) != w) return fail("owner(first(w)) != w", w);
-    if (sp.first(w) < sp.first(w + 1) && sp.owner(sp.first(w + 1) - 1) != w) return fail("owner(last(w)) != w", w);
     const int len = sp.first(w + 1) - sp.first(w);
-    if (len < sp.per || len > sp.per + 1) return fail("uneven share", w, len, sp.per);
+    if (len < 0) return fail("shares not monotonic", w);
+    if (len == 0) continue;
+    ++nonempty;
+    if (sp.owner(sp.first(w)) != w) return fail("owner(first(w)) != w", w);
+    if (sp.owner(sp.first(w + 1) - 1) != w) return fail("owner(last(w)) != w", w);
+    longest = len > longest ? len : longest;
+    if (sp.first(w + 1) < total) shortest = len < shortest ? len : shortest;  // all but the last non-empty share
+  }
+  if (total > 0) {
+    if (nonempty > 1 && longest - shortest > 1) return fail("uneven shares", longest, shortest);
+    // no share is longer than an even division over the aimed-at number of shares would make it
+    if (longest > (total + s.target - 1) / s.target) return fail("a share is longer than total / target", longest, total, s.target);
+    if (s.target < s.nshares && nonempty > 1 && total >= 2 * s.nshares && longest != shortest)
+      return fail("room for more shares, but they are not equally long", longest, shortest);
   }
   // coverage[unit][block] = number of segments that hold it; holders[unit] = shares with a segment of it
   std::vector<std::vector<int>> coverage((size_t)s.B * s.Hkv);
@@ -129,6 +141,7 @@ int main(int argc, char** argv) {
     s.Lcap = it % 3 == 0 ? uni(1, 200) : uni(200, 9000);
     const int nshares_choices[] = {16, 64, 100, 256, 448, 768, 1020, 1024, 2048, 8192};
     s.nshares = nshares_choices[uni(0, 9)];
+    s.target = it % 2 == 0 ? s.nshares : imax(1, s.nshares * 3 / 4);
     s.pad = uni(0, kMaxPad);
     s.pad_before = uni(0, s.pad);
     s.span = it % 4 == 0 ? uni(0, s.Lcap + 50) : 0;
@@ -140,8 +153,8 @@ int main(int argc, char** argv) {
       if (it % 11 == 0) ctx[b] = uni(0, imin(s.Lcap, 40));  // many tiny units
     }
     if (check_case(s, ctx, dl)) {
-      printf("case %d: B=%d Hkv=%d kmax=%d Lcap=%d nshares=%d pad=%d pad_before=%d span=%d\n", it, s.B, s.Hkv, s.kmax, s.Lcap,
-             s.nshares, s.pad, s.pad_before, s.span);
+      printf("case %d: B=%d Hkv=%d kmax=%d Lcap=%d nshares=%d target=%d pad=%d pad_before=%d span=%d\n", it, s.B, s.Hkv, s.kmax,
+             s.Lcap, s.nshares, s.target, s.pad, s.pad_before, s.span);
       return 1;
     }
     ++done;

@@ -103,9 +103,9 @@ def check_plan(desc, ctx_len, draft_len, flags, padded_len, expect_shares=None):
     for w in range(nshares):
         segs = segments_of(plan, w)
         rec = plan["records"][w]
-        if len(segs) > 2:  # overflow entries are handed out in share order, without gaps
-            assert int(rec[17]) == seen_overflow
-            seen_overflow += len(segs) - 2
+        if len(segs) > 2:  # a share's run of overflow entries: behind the runs of the shares before it, inside the list
+            assert int(rec[17]) >= seen_overflow
+            seen_overflow = int(rec[17]) + len(segs) - 2
         assert seen_overflow <= nshares + B * Hkv
         prev = -1
         real = 0
@@ -133,13 +133,16 @@ def check_plan(desc, ctx_len, draft_len, flags, padded_len, expect_shares=None):
             continue
         lo, hi = int(plan["owners"][unit]) & 0xFFFF, (int(plan["owners"][unit]) >> 16) & 0xFFFF
         assert holders[unit] == list(range(lo, hi + 1)), f"unit {unit}: holders {holders[unit]} vs {lo}..{hi}"
-    # balance: shares differ by at most one entry; a unit's virtual blocks (pad) are the only other difference
+    # balance: the shares that hold work differ by at most one entry (real blocks plus a unit's `pad` virtual
+    # ones), except the last one, which takes what is left
     total_real = sum(nblk) * Hkv
     assert sum(real_per_share) == total_real
     pad = int(hdr[6])
     if total_real:
-        per = (total_real + pad * sum(1 for x in nblk if x) * Hkv) // nshares
-        assert max(real_per_share) <= per + 1
+        entries = total_real + pad * sum(1 for x in nblk if x) * Hkv
+        assert int(hdr[10]) == entries
+        busy = [r for r in real_per_share if r]
+        assert max(busy) <= -(-entries // min(len(busy), nshares)) + 1
     return plan
 
 

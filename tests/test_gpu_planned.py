@@ -40,8 +40,10 @@ def assert_same_plan(dev_bytes, host_bytes, B, Hkv):
     d, h = parse_plan(dev_bytes, B, Hkv), parse_plan(host_bytes, B, Hkv)
     np.testing.assert_array_equal(d["hdr"], h["hdr"])
     np.testing.assert_array_equal(d["records"], h["records"])
-    used = sum(max(0, int(r[16]) - 2) for r in h["records"])
-    np.testing.assert_array_equal(d["overflow"][:used], h["overflow"][:used])
+    for r in h["records"]:  # the overflow entries the records point at
+        if int(r[16]) > 2:
+            lo, hi = int(r[17]), int(r[17]) + int(r[16]) - 2
+            np.testing.assert_array_equal(d["overflow"][lo:hi], h["overflow"][lo:hi])
     for part in ("seq_L", "seq_nq", "seq_inc", "owners"):
         np.testing.assert_array_equal(d[part], h[part])
 
