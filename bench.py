@@ -138,7 +138,7 @@ class Step:
         rec(0)
         planned = not (args.unplanned or args.separate_append)
         if planned:
-            bass.bass_attention_plan(self.desc, self.ctx, self.nq, bass.PLAN_APPEND, 0, self.plan, self.status)
+            self.launch_plan()
         rec(1)
         for l in self.layers:
             if args.separate_append:
@@ -153,8 +153,7 @@ class Step:
                                                    None, self.ws, self.status)
         rec(2)
         if self.with_accept:
-            bass.bass_spec_accept(self.p, self.q, self.tok, self.ndr, self.u, self.n_accept, self.next_token,
-                                  self.ctx_scratch, self.status)
+            self.launch_accept()
         rec(3)
 
     def capture(self):
@@ -214,7 +213,31 @@ class Step:
             plan_ms.append(ev[0].elapsed_time(ev[1]))
             attn_ms.append(ev[1].elapsed_time(ev[2]) / self.NL)
             accept_ms.append(ev[2].elapsed_time(ev[3]))
-        return 1e3 * float(np.mean(plan_ms)), 1e3 * float(np.mean(attn_ms)), 1e3 * float(np.mean(accept_ms))
+        # a single launch between two events mostly shows the events: the plan and the acceptance are timed
+        # as runs of back-to-back launches instead (both are idempotent on these inputs)
+        planned = not (self.args.unplanned or self.args.separate_append)
+        plan_us = self.repeated(self.launch_plan) if planned else 1e3 * float(np.mean(plan_ms))
+        accept_us = self.repeated(self.launch_accept) if self.with_accept else 1e3 * float(np.mean(accept_ms))
+        return plan_us, 1e3 * float(np.mean(attn_ms)), accept_us
+
+    def repeated(self, launch, n=16, sweeps=3):
+        """Microseconds per launch of n back-to-back launches (HIP events around the run), last of `sweeps` runs."""
+        torch = self.torch
+        for _ in range(sweeps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                launch()
+            e1.record()
+            torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / n
+
+    def launch_plan(self):
+        self.bass.bass_attention_plan(self.desc, self.ctx, self.nq, self.bass.PLAN_APPEND, 0, self.plan, self.status)
+
+    def launch_accept(self):
+        self.bass.bass_spec_accept(self.p, self.q, self.tok, self.ndr, self.u, self.n_accept, self.next_token,
+                                   self.ctx_scratch, self.status)
 
     def kv_bytes(self):
         kv = self.w.kv_bytes  # per layer
@@ -348,7 +371,7 @@ def main():
               "GBps": round(value, 1), "attention_call_us": round(attn_us, 2), "frac": round(frac_of(kv_bytes, attn_us), 4)}]
     ceiling_us = ceiling_bytes = None
     others = {}
-    warp_us = None
+    warp_us = two_us = fused_us = None
     if not args.only_headline:
         ceiling_us, ceiling_bytes = step.ceiling(6, 768)
         # ---- the other draws of the same recipe: same slabs, same graph, lengths and contents redrawn ----
@@ -380,7 +403,18 @@ def main():
             torch.cuda.synchronize()
             warp_ms.append(e0.elapsed_time(e1) / reps)
         warp_us = 1e3 * warp_ms[-1]
-        del lt, ld, pw, qw
+        # ... and the call that goes from the logits to the acceptance without storing p and q
+        wa_ws = torch.empty(bass.bass_warp_accept_workspace_bytes(acc.B, acc.kmax, acc.V), dtype=torch.uint8, device=dev)
+        n_acc2, nxt2 = torch.zeros_like(step.n_accept), torch.zeros_like(step.next_token)
+        two_us = step.repeated(lambda: (bass.bass_warp_probs(lt, 0.2, 0.95, pw, step.status),
+                                        bass.bass_warp_probs(ld, 0.2, 0.95, qw, step.status),
+                                        bass.bass_spec_accept(pw, qw, step.tok, step.ndr, step.u, n_acc2, nxt2, None, step.status)),
+                               n=reps)
+        want = (n_acc2.clone(), nxt2.clone())
+        fused_us = step.repeated(lambda: bass.bass_warp_accept(lt, ld, 0.2, 0.95, step.tok, step.ndr, step.u, n_acc2, nxt2,
+                                                               wa_ws, None, step.status), n=reps)
+        assert torch.equal(n_acc2, want[0]) and torch.equal(nxt2, want[1]), "bass_warp_accept differs from the two calls"
+        del lt, ld, pw, qw, wa_ws
 
     del step
     torch.cuda.empty_cache()
@@ -443,6 +477,8 @@ def main():
         "attention_plan_us": round(plan_us, 2),
         "spec_accept_us": round(accept_us, 2),
         "logit_warp_us": None if warp_us is None else round(warp_us, 2),
+        "logits_to_acceptance_us": None if fused_us is None else {
+            "bass_warp_probs x 2 + bass_spec_accept": round(two_us, 2), "bass_warp_accept": round(fused_us, 2)},
         "roofline": {
             "kernel": ("verify_attn_bf16<128,1,int8> (quantizing append + streaming + split-context reduction, one launch)"
                        if args.kv_int8 else

@@ -273,6 +273,30 @@ int bass_warp_probs(int32_t R, int32_t V, const float* logits, float temperature
                     float* probs, int32_t* dev_status, void* stream);
 
 /*
+ * Logits front end and acceptance in one call: the result of bass_warp_probs on the main- and the
+ * draft-model logits followed by bass_spec_accept on the rows it made (Section 2.2; temperature and
+ * top-p as in the captions of Section 4's tables), without storing any probability row.  n_accept,
+ * next_token, ctx_len and the status bits are identical, bit for bit, to those of the two calls.
+ *   logits_main  [B, kmax+1, V] fp32 (device)  main-model logits; row i judges draft i
+ *   logits_draft [B, kmax,   V] fp32 (device)  draft-model logits (may be NULL if kmax = 0)
+ *   temperature, top_p                         as in bass_warp_probs
+ *   draft_tok, n_draft, u, n_accept, next_token, ctx_len   as in bass_spec_accept
+ *   workspace    device scratch of at least bass_warp_accept_workspace_bytes(B, kmax, V) bytes,
+ *                256-byte aligned, contents irrelevant on entry (per-row summaries of the warp,
+ *                partial sums of the draw); calls that share one workspace must not overlap
+ * Two launches: one workgroup per row of logits, then several workgroups per sequence for the
+ * accept tests and the draw.  temperature > 0, top_p > 0, V <= 2^19, B <= 65535; otherwise
+ * BASS_ERR_INVALID_ARG / BASS_ERR_UNSUPPORTED.  bass_warp_accept_workspace_bytes returns 0 for
+ * arguments the call would refuse.
+ */
+size_t bass_warp_accept_workspace_bytes(int32_t B, int32_t kmax, int32_t V);
+int bass_warp_accept(int32_t B, int32_t kmax, int32_t V, const float* logits_main,
+                     const float* logits_draft, float temperature, float top_p,
+                     const int32_t* draft_tok, const int32_t* n_draft, const float* u,
+                     int32_t* n_accept, int32_t* next_token, int32_t* ctx_len, void* workspace,
+                     size_t workspace_bytes, int32_t* dev_status, void* stream);
+
+/*
  * Draft-length heuristic (Algorithm 1 of the paper; HOST code, HOST pointers): picks the
  * uniform draft length of the next speculative step from the numbers of drafts the sequences
  * accepted in the last one.  If some sequence accepted all l_draft drafts the length grows by

@@ -25,6 +25,7 @@ EXPORTS = (
     "bass_version", "bass_status_string", "bass_kv_cache_bytes", "bass_verify_attention_workspace_bytes",
     "bass_kv_append", "bass_kv_gather", "bass_kv_gather_int8", "bass_verify_attention", "bass_verify_attention_pad",
     "bass_verify_attention_split", "bass_append_verify_attention", "bass_spec_accept", "bass_warp_probs",
+    "bass_warp_accept", "bass_warp_accept_workspace_bytes",
     "bass_set_attention_waves", "bass_draft_len_init", "bass_next_draft_len",
     "bass_attention_plan_bytes", "bass_attention_plan", "bass_attention_plan_host", "bass_verify_attention_planned",
     "bass_bench_stream_read", "bass_verify_attention_noalloc",
@@ -91,6 +92,11 @@ def lib():
         L.bass_spec_accept.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bass_warp_probs.restype = ctypes.c_int
         L.bass_warp_probs.argtypes = [i32, i32, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp]
+        L.bass_warp_accept_workspace_bytes.restype = ctypes.c_size_t
+        L.bass_warp_accept_workspace_bytes.argtypes = [i32, i32, i32]
+        L.bass_warp_accept.restype = ctypes.c_int
+        L.bass_warp_accept.argtypes = [i32, i32, i32, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp,
+                                       ctypes.c_size_t, vp, vp]
         L.bass_draft_len_init.restype = None
         L.bass_draft_len_init.argtypes = [ctypes.POINTER(DraftLenState), i32]
         L.bass_next_draft_len.restype = i32
@@ -412,6 +418,32 @@ def bass_warp_probs(logits, temperature, top_p, probs, dev_status=None, stream=N
     _check(lib().bass_warp_probs(R, V, lp, ctypes.c_float(float(temperature)), ctypes.c_float(float(top_p)), pp,
                                  _dev(dev_status, "dev_status", torch.int32, optional=True), _stream(stream)),
            "bass_warp_probs")
+
+
+def bass_warp_accept_workspace_bytes(B, kmax, V):
+    return int(lib().bass_warp_accept_workspace_bytes(int(B), int(kmax), int(V)))
+
+
+def bass_warp_accept(logits_main, logits_draft, temperature, top_p, draft_tok, n_draft, u, n_accept, next_token,
+                     workspace, ctx_len=None, dev_status=None, stream=None):
+    """logits_main [B, kmax+1, V], logits_draft [B, kmax, V] fp32 -> n_accept, next_token (ctx_len advanced):
+    bass_warp_probs on both tensors followed by bass_spec_accept, without the probability rows."""
+    torch = _torch()
+    if logits_main is None or logits_main.dim() != 3:
+        raise ValueError("logits_main must be [B, kmax+1, V]")
+    B, k1, V = logits_main.shape
+    kmax = k1 - 1
+    f32, i32 = torch.float32, torch.int32
+    wsp = _dev(workspace, "workspace", torch.uint8)
+    _check(lib().bass_warp_accept(
+        B, kmax, V, _dev(logits_main, "logits_main", f32),
+        _dev(logits_draft, "logits_draft", f32, (B, kmax, V), optional=(kmax == 0)),
+        ctypes.c_float(float(temperature)), ctypes.c_float(float(top_p)),
+        _dev(draft_tok, "draft_tok", i32, (B, kmax), optional=(kmax == 0)), _dev(n_draft, "n_draft", i32, (B,)),
+        _dev(u, "u", f32, (B, kmax + 1)), _dev(n_accept, "n_accept", i32, (B,)),
+        _dev(next_token, "next_token", i32, (B,)), _dev(ctx_len, "ctx_len", i32, (B,), optional=True),
+        wsp, ctypes.c_size_t(workspace.numel()), _dev(dev_status, "dev_status", i32, optional=True), _stream(stream)),
+        "bass_warp_accept")
 
 
 # ---- allocation helpers (plumbing; no arithmetic) ----------------------------------------------

@@ -1143,6 +1143,13 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       if (lastA) zero_rows<D>(p, uA.b, uA.kvh, uA.nq * p.g, lane);
       if (lastB) zero_rows<D>(p, uB.b, uB.kvh, uB.nq * p.g, lane);
     };
+    // The next segments were requested right behind the first block and are here with it; kept as scalars
+    // from here on, they do not take vector registers away from the ring.
+    Segment next_sa, next_sb;
+    auto next_arrived = [&]() {
+      next_sa = arrived_segment(nextA);
+      next_sb = arrived_segment(nextB);
+    };
     if constexpr (NT <= 2) {
       // three-deep register ring: two blocks (32 KiB per wavefront) in flight while one is computed
       Regs r1, r2;  // r0 is on its way already
@@ -1152,6 +1159,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         stage_rest();
       }
       clear_unused();
+      next_arrived();
       for (int s = 0; s < n; s += 3) {
         fetch(r2, s + 2);
         step(r0, s);
@@ -1168,6 +1176,7 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         stage_rest();
       }
       clear_unused();
+      next_arrived();
       for (int s = 0; s < n; s += 2) {
         fetch(r1, s + 1);
         step(r0, s);
@@ -1184,8 +1193,8 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
       if (mergeA || mergeB) combine_jobs<D>(p, ja, mergeA, jb, mergeB, lane);
     }
     si = si_next;
-    sa = arrived_segment(nextA);
-    sb = arrived_segment(nextB);
+    sa = next_sa;
+    sb = next_sb;
   } while (si < nseg);
   if (!ok) {
     report_mismatch(p, w == 0 && lane == 0);

@@ -8,7 +8,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (bass_kv_gather_int8, bass_warp_probs, AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
+from . import (bass_kv_gather_int8, bass_warp_probs, bass_warp_accept, bass_warp_accept_workspace_bytes, AttnDesc, alloc_kv_cache, alloc_workspace, bass_append_verify_attention, bass_kv_append, bass_kv_gather,
                bass_spec_accept, bass_verify_attention, bass_verify_attention_pad, bass_verify_attention_split, make_desc)
 
 
@@ -122,6 +122,37 @@ def run_accept_workload(a, ctx_len=None, device="cuda"):
     ctx = None if ctx_len is None else i32(ctx_len, device)
     bass_spec_accept(to_device(a.p, device), to_device(a.q, device), i32(a.draft_tok, device).reshape(B, a.kmax),
                      i32(a.n_draft, device), to_device(a.u, device), n_accept, next_token, ctx, status)
+    torch.cuda.synchronize()
+    out = (to_host(n_accept), to_host(next_token), int(status.item()))
+    return out if ctx is None else out + (to_host(ctx),)
+
+
+def run_warp_accept(logits_main, logits_draft, temperature, top_p, draft_tok, n_draft, u, ctx_len=None, device="cuda",
+                    two_calls=False):
+    """bass_warp_accept on host logits, or (two_calls) bass_warp_probs on both tensors followed by
+    bass_spec_accept; returns (n_accept, next_token, status[, ctx_len]) on the host."""
+    lm = to_device(np.asarray(logits_main, np.float32), device)
+    B, k1, V = lm.shape
+    kmax = k1 - 1
+    ld = to_device(np.asarray(logits_draft, np.float32), device) if kmax else None
+    tok = i32(draft_tok, device).reshape(B, kmax) if kmax else None
+    n_accept = torch.full((B,), -1, dtype=torch.int32, device=device)
+    next_token = torch.full((B,), -1, dtype=torch.int32, device=device)
+    status = torch.zeros(1, dtype=torch.int32, device=device)
+    ctx = None if ctx_len is None else i32(ctx_len, device)
+    uu, nd = to_device(np.asarray(u, np.float32), device), i32(n_draft, device)
+    if two_calls:
+        p = torch.full_like(lm, float("nan"))
+        bass_warp_probs(lm, temperature, top_p, p, status)
+        q = None
+        if kmax:
+            q = torch.full_like(ld, float("nan"))
+            bass_warp_probs(ld, temperature, top_p, q, status)
+        bass_spec_accept(p, q, tok, nd, uu, n_accept, next_token, ctx, status)
+    else:
+        # poisoned workspace: the call may not depend on its contents
+        ws = torch.full((bass_warp_accept_workspace_bytes(B, kmax, V),), 0xA5, dtype=torch.uint8, device=device)
+        bass_warp_accept(lm, ld, temperature, top_p, tok, nd, uu, n_accept, next_token, ws, ctx, status)
     torch.cuda.synchronize()
     out = (to_host(n_accept), to_host(next_token), int(status.item()))
     return out if ctx is None else out + (to_host(ctx),)

@@ -17,7 +17,9 @@ kernel, grid size and register count).
 
 `logits` calls bass_warp_probs on the rows of one verification step (workloads.make_logits: 8 x 6 main-model
 and 8 x 5 draft-model rows of 50 000 logits) at three settings: the paper's temperature 0.2 / top-p 0.95,
-flat rows (1.0 / 0.9) and the plain softmax (1.0 / 1.0) -- or at the one setting given.
+flat rows (1.0 / 0.9) and the plain softmax (1.0 / 1.0) -- or at the one setting given; then, at the first
+setting, bass_spec_accept on the rows made and bass_warp_accept on the logits (drafts: the draft model's
+most likely tokens).
 
 Needs the GPU and the built library (except `summarize`).
 """
@@ -115,6 +117,23 @@ def logits(args):
         torch.cuda.synchronize()
         print(f"T={T} top_p={top_p}: {e0.elapsed_time(e1) * 1e3 / args.reps:.1f} us per pair of launches (48 + 40 rows)",
               flush=True)
+    # the acceptance on the rows made last, and the call that goes from the logits to the acceptance without them
+    T, top_p = settings[0]
+    tok = lt[:, :5].argmax(dim=-1).to(torch.int32).contiguous()
+    nd = torch.full((8,), 5, dtype=torch.int32, device="cuda:0")
+    u = torch.rand((8, 6), device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(3))
+    n_acc, nxt = torch.zeros_like(nd), torch.zeros_like(nd)
+    ws = torch.empty(bass.bass_warp_accept_workspace_bytes(8, 5, 50000), dtype=torch.uint8, device="cuda:0")
+    bass.bass_warp_probs(lt, T, top_p, pw, status)
+    bass.bass_warp_probs(ld, T, top_p, qw, status)
+    for _ in range(args.reps + 1):
+        bass.bass_spec_accept(pw, qw, tok, nd, u, n_acc, nxt, None, status)
+    two = (n_acc.clone(), nxt.clone())
+    for _ in range(args.reps + 1):
+        bass.bass_warp_accept(lt, ld, T, top_p, tok, nd, u, n_acc, nxt, ws, None, status)
+    torch.cuda.synchronize()
+    assert torch.equal(n_acc, two[0]) and torch.equal(nxt, two[1])
+    print(f"bass_warp_accept at T={T} top_p={top_p}: accepted {n_acc.tolist()}, same as the two calls", flush=True)
 
 
 def summarize(args):
@@ -122,7 +141,7 @@ def summarize(args):
     agg = collections.defaultdict(list)
     for r in rows:
         name = r["Kernel_Name"]
-        if "bass::" not in name:
+        if "bass::" not in name and "bass" not in name:
             continue
         key = (name.split("(")[0].replace("void ", ""), r.get("Grid_Size_X") or r.get("Grid_Size"),
                r.get("VGPR_Count") or r.get("Arch_VGPR_Count"))

@@ -58,7 +58,8 @@ def test_small_vocabularies(hip, T, top_p):
         logits = (rng.standard_normal((6, V)) * 3).astype(np.float32)
         got, status = hip.run_warp_probs(logits, T, top_p)
         assert status == 0
-        check_rows(logits, T, top_p, got)
+        # an open decision needs a cumulative mass within 2e-5 of top_p, or a near-tie at the cut: rare
+        assert check_rows(logits, T, top_p, got) <= 1
 
 
 @pytest.mark.parametrize("T,top_p", [(0.2, 0.95), (1.0, 0.9)])
@@ -84,7 +85,7 @@ def test_full_step_shapes_and_determinism(hip):
         assert (got.view(np.uint32) == again.view(np.uint32)).all()      # integer masses: same bits every run
     # flat distribution at a high temperature: the nucleus holds most of the vocabulary
     got, _ = hip.run_warp_probs(lt[:2], 5.0, 0.9)
-    check_rows(lt[:2], 5.0, 0.9, got)
+    assert check_rows(lt[:2], 5.0, 0.9, got) <= 1
 
 
 def test_ties_are_taken_by_token_id(hip):
