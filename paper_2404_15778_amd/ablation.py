@@ -8,7 +8,9 @@ close, moderately spread (the cfg2 recipe) and widely spread (the cfg3 recipe), 
     python -m paper_2404_15778_amd.ablation [--layers 16] [--reps 5] [--seed 0]
 
 One JSON line per (scenario, variant): microseconds per layer call, useful KV bytes per second, and
-the bytes the variant actually has to read.  Needs the GPU and the built library.
+the bytes the variant actually has to read.  "ragged", "pad" and "split" are the entry points that take the
+lengths (every call plans its own work division: one small launch in front of each attention launch);
+"ragged, one plan" and "pad, one plan" make the division once for all layers, as a verification step does.  Needs the GPU and the built library.
 """
 from __future__ import annotations
 
@@ -63,10 +65,17 @@ def run(name, ctx_len, draft_len, layers, reps, dev):
     blocks = lambda n: -(-int(n) // 32) * 32
     read = {"ragged": sum(blocks(t) for t in total) * row_bytes, "split": sum(blocks(t) for t in total) * row_bytes,
             "pad": B * blocks(longest) * row_bytes}
+    # the work division of a step made once for all its layers (ragged and padded), as a verification step does
+    plan_r, plan_p = bass.alloc_plan(desc, dev), bass.alloc_plan(desc, dev)
+    bass.bass_attention_plan(desc, ctx, nq, 0, 0, plan_r, status)
+    bass.bass_attention_plan(desc, ctx, nq, 0, longest, plan_p, status)
+    read["ragged, one plan"], read["pad, one plan"] = read["ragged"], read["pad"]
     calls = {
         "ragged": lambda Kc, Vc: bass.bass_verify_attention(desc, Q, Kc, Vc, ctx, nq, O, None, ws, status),
         "pad": lambda Kc, Vc: bass.bass_verify_attention_pad(desc, Q, Kc, Vc, ctx, nq, longest, O, None, ws, status),
         "split": lambda Kc, Vc: bass.bass_verify_attention_split(desc, Q, Kc, Vc, ctx, nq, O, None, ws, status),
+        "ragged, one plan": lambda Kc, Vc: bass.bass_verify_attention_planned(desc, Q, None, None, Kc, Vc, plan_r, O, None, ws, status),
+        "pad, one plan": lambda Kc, Vc: bass.bass_verify_attention_planned(desc, Q, None, None, Kc, Vc, plan_p, O, None, ws, status),
     }
     ref = None
     for variant, call in calls.items():
@@ -87,6 +96,7 @@ def run(name, ctx_len, draft_len, layers, reps, dev):
         print(json.dumps({"scenario": name, "variant": variant, "us_per_layer": round(best, 2),
                           "useful_kv_GBps": round(useful / best / 1e3, 1), "useful_kv_bytes": useful,
                           "bytes_read": read[variant], "launches_per_layer": B if variant == "split" else 1,
+                          "plan_launches_per_layer": 0 if "one plan" in variant else (B if variant == "split" else 1),
                           "ctx_min": int(ctx_len.min()), "ctx_max": int(ctx_len.max())}), flush=True)
     assert int(status.item()) == 0
 

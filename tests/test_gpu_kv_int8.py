@@ -148,6 +148,30 @@ def test_int8_query_rows_of_zeros_and_extreme_query_rows(hip):
     np.testing.assert_allclose(O[0, 1, 2], Vhat[0, :70 + 2, 1].mean(axis=0), atol=TOL)
 
 
+def test_int8_deviation_from_the_unquantized_attention(hip):
+    # What the INT8 cache costs in accuracy: the attention over it against the fp64 attention over the ORIGINAL
+    # bf16 inputs (not over the represented values as in the parity checks above), at the benchmark shape, on
+    # sampled rows.  N(0,1) keys and values, D = 128: a code step is about amax / 127 = 0.02 of a row's range,
+    # so scores move by about 0.01 and outputs (|O| about 0.05 at these lengths) by about 1e-3.
+    w = wl.config2(0)
+    O, lse, status, _ = run(hip, w, two_step=False)
+    assert status == 0
+    rng = np.random.default_rng(8)
+    worst_o = worst_l = 0.0
+    rel = []
+    for _ in range(32):
+        b = int(rng.integers(w.B))
+        i, h = int(rng.integers(w.draft_len[b])), int(rng.integers(w.Hq))
+        ref, lref = oracle.verify_attention_row(w.Q, w.K, w.V, b, i, h, int(w.ctx_len[b]), w.scale)
+        err = float(np.abs(O[b, i, h] - ref).max())
+        worst_o, worst_l = max(worst_o, err), max(worst_l, abs(float(lse[b, i, h]) - lref))
+        rel.append(float(np.linalg.norm(O[b, i, h] - ref) / np.linalg.norm(ref)))
+    print(f"INT8 cache against unquantized inputs (cfg2, 32 rows): max |O - O_ref| = {worst_o:.2e}, "
+          f"max |lse - lse_ref| = {worst_l:.2e}, relative L2 error of a row: median {np.median(rel):.2e}, "
+          f"max {max(rel):.2e}", flush=True)
+    assert worst_o <= 5e-3 and worst_l <= 2e-2 and max(rel) <= 5e-2
+
+
 def test_int8_cache_is_about_half_the_bytes(hip):
     import paper_2404_15778_amd as bass
     a = bass.bass_kv_cache_bytes(bass.make_desc(8, 6, 32, 32, 128, 2056, "bf16", 1.0))
