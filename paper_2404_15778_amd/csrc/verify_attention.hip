@@ -975,6 +975,29 @@ __device__ inline void store_partial(const AttnParams& p, const Unit& u, int w, 
   }
 }
 
+// A unit that this wavefront streamed alone needs no exchange: its output rows are written straight from the
+// registers.  The arithmetic is that of the merge of a single partial (weight 2^0 = 1, the same reciprocal and
+// logarithm), so a unit's result does not depend on which of the two ways it took.
+template <int D, int NT>
+__device__ inline void finalize_single(const AttnParams& p, const Unit& u, const RowState<D, NT>& st, int col, int grp,
+                                       int row0 = 0) {
+  const int rows = u.nq * p.g;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const float L = fmaf(rows4_sum(st.l[nt]), 1.0f, 0.f);
+    const int rrow = row0 + nt * 16 + col;
+    if (rrow < rows) {
+      const float M = st.m[nt];
+      const float invL = __builtin_amdgcn_rcpf(L);
+      const int i = row_token(p, rrow), hg = rrow - i * p.g;
+      const size_t orow = ((size_t)u.b * p.kmax + i) * p.Hq + u.kvh * p.g + hg;
+#pragma unroll
+      for (int mt = 0; mt < D / 16; ++mt) *(f32x4*)(p.O + orow * D + 16 * mt + 4 * grp) = st.acc[nt][mt] * invL;
+      if (p.lse && grp == 0) p.lse[orow] = (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f;
+    }
+  }
+}
+
 template <int D, int NT, bool kI8 = false>
 __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
   // uint4 per block: 32 tokens of D bf16, or of D INT8 codes followed by 32 fp32 scales
@@ -1184,12 +1207,26 @@ __global__ __launch_bounds__(256) void verify_attn_bf16(AttnParams p) {
         if (s + 1 < n) step(r1, s + 1);
       }
     }
-    if (hasB) store_partial<D, NT>(p, uA, w, parked, col, grp);
-    store_partial<D, NT>(p, hasB ? uB : uA, w, st, col, grp);
-    if (p.fused_reduce) {  // otherwise a second launch merges the partials
+    // A unit that lies wholly inside this share (common with many short sequences) is finished from the
+    // registers; the others leave a partial, and the wavefront that delivers a unit's last partial merges.
+    // (With a merge launch of its own -- more than one query tile -- every unit leaves a partial.)
+    const bool soloA = p.fused_reduce && ja.w_lo == ja.w_hi;
+    const bool soloB = p.fused_reduce && hasB && jb.w_lo == jb.w_hi;
+    if (hasB) {
+      if (soloA) finalize_single<D, NT>(p, uA, parked, col, grp);
+      else store_partial<D, NT>(p, uA, w, parked, col, grp);
+      if (soloB) finalize_single<D, NT>(p, uB, st, col, grp);
+      else store_partial<D, NT>(p, uB, w, st, col, grp);
+    } else {
+      if (soloA) finalize_single<D, NT>(p, uA, st, col, grp);
+      else store_partial<D, NT>(p, uA, w, st, col, grp);
+    }
+    const bool exchA = !soloA, exchB = hasB && !soloB;
+    if (p.fused_reduce && (exchA || exchB)) {
       partial_stores_done();
-      bool mergeA, mergeB;
-      arrive(p, lane, ja, mergeA, hasB, jb, mergeB);
+      bool mergeA = false, mergeB = false, unused;
+      if (exchA) arrive(p, lane, ja, mergeA, exchB, jb, mergeB);
+      else arrive(p, lane, jb, mergeB, false, jb, unused);
       if (mergeA || mergeB) combine_jobs<D>(p, ja, mergeA, jb, mergeB, lane);
     }
     si = si_next;
