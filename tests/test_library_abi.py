@@ -103,3 +103,21 @@ def test_kernel_times_summarize_reads_a_kernel_trace(tmp_path, capsys):
     out = capsys.readouterr().out.strip().splitlines()
     assert len(out) == 1 and "verify_attn_bf16<128, 1, false>" in out[0]
     assert "n=2" in out[0] and "avg 31.00 us" in out[0] and "min 30.00 us" in out[0]
+
+
+def test_recorded_hbm_traffic_belongs_to_this_library_version():
+    """bench.py reports roofline.traffic only from a counter summary made with the library it times: the
+    summary under profiles/ must carry the current version, and its figure must be a plausible multiple of
+    the algorithmic bytes of the benchmark launch (cfg2, seed 0)."""
+    import importlib.util
+    import workloads as wl
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    traffic = bench.measured_traffic(bass.bass_version())
+    assert traffic is not None, "profiles/verify_attn_bf16_cfg2_hbm_traffic.txt was made with another library version"
+    w = wl.config2(0, tensors=False)
+    algorithmic = int((w.ctx_len + w.draft_len).sum()) * 2 * w.Hkv * w.D * 2
+    assert algorithmic == 158515200
+    assert 1.0 <= traffic / algorithmic <= 1.15
+    assert bench.measured_traffic(bass.bass_version() + 1) is None
