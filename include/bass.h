@@ -323,7 +323,8 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
  * clamped to [64, 8192]; 0 restores the defaults, which depend on the call: 768 for bf16 / fp32 with up
  * to 16 query rows per kv head, 1024 for INT8 caches, 256 workgroups of four wavefronts for bf16 caches
  * with more query rows (a setting W gives W / 2 workgroups there).  Returns the value in effect for
- * the first of these cases.
+ * the first of these cases.  (A launch of 768 wavefronts runs as 256 workgroups of three, one per compute
+ * unit; every other count as workgroups of four.)
  */
 int bass_set_attention_waves(int waves);
 
@@ -349,7 +350,8 @@ int bass_verify_attention_noalloc(const bass_attn_desc* desc, const void* Q, con
  * Measurement aid (not part of the verification step): a plain streaming read of the first
  * floor(bytes_each / 8192) * 8192 bytes of K and of V with the access pattern of the attention kernel
  * (`waves` wavefronts, each a contiguous share of 8 KiB K blocks and 8 KiB V blocks, 1 KiB per
- * wavefront load instruction, non-temporal, two blocks in flight) and no arithmetic: the time the memory
+ * wavefront load instruction, non-temporal, two blocks in flight, the workgroup shape of an attention
+ * launch of as many wavefronts) and no arithmetic: the time the memory
  * system needs for the bytes of an attention launch, which is what Section 3.2 says the step is bound by.
  * K, V: device, 16-byte aligned; waves: a multiple of 4 in [4, 8192]; sink: device, >= waves words, or
  * NULL.  Returns the bytes read per launch (K and V together), or a negative BASS_ERR_* code.

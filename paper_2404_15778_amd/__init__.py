@@ -64,6 +64,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2404_15778_amd.build` "
                                "(there is no fallback path)")
+        # One HIP runtime per process: torch's wheel carries its own copy of libamdhip64, which libbass.so
+        # (linked against the soname) shares only if torch has loaded it first.  Loaded the other way round
+        # the process holds two runtimes, and kernels launched through one on memory of the other fail.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         dp = ctypes.POINTER(AttnDesc)

@@ -117,7 +117,13 @@ inline int check_desc(const bass_attn_desc* d) {
 // list is divided, and the virtual blocks of a unit.  The plan of a step and the launches that
 // consume it derive it from the same inputs.
 // ---------------------------------------------------------------------------------------
-constexpr int kWavesPerWorkgroup = 4;
+constexpr int kWavesPerWorkgroup = 4;  // also the grain of a launch's wavefront count
+constexpr int kComputeUnits = 256;     // MI355X
+// Wavefronts per workgroup of a launch whose wavefronts each fill a SIMD's registers (one workgroup per
+// compute unit at a time).  Four, except where three put exactly one workgroup on every compute unit: 768
+// wavefronts as 256 x 3 measured 2 % shorter attention launches than as 192 x 4 with 64 units idle (two per
+// workgroup, 384 workgroups: 7 % longer; one: 1 % shorter).
+inline int waves_per_workgroup(int nwaves) { return nwaves == 3 * kComputeUnits ? 3 : kWavesPerWorkgroup; }
 constexpr int kAppendPad = 3;     // virtual blocks per unit when the append is fused (measured best: 3)
 constexpr int kPlainPad = 2;      // ... and when it is not (the unit's last blocks are the masked, slower ones)
 constexpr int kAppendBefore = 1;  // how many of those sit in front of the unit's last real block (one-tile matrix-core

@@ -37,7 +37,7 @@ __device__ inline unsigned stream_consume(const StreamBlock& r) {
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* k, const uint4* v, int nblocks, int nwaves,
                                                           uint32_t* sink) {
   const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerWorkgroup + (threadIdx.x >> 6));
+  const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
   const Split sp = make_split(nblocks, nwaves);
   const int base = sp.first(w), n = sp.first(w + 1) - base;
   // all fetches unconditional, as in the attention kernel; one past the end re-reads 16 bytes of the
@@ -69,8 +69,9 @@ extern "C" int64_t bass_bench_stream_read(const void* K, const void* V, size_t b
   if (((uintptr_t)K & 15) != 0 || ((uintptr_t)V & 15) != 0) return BASS_ERR_INVALID_ARG;
   const size_t nblocks = bytes_each / 8192;
   if (nblocks < 1 || nblocks > 0x7fffffff) return BASS_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(bass::stream_read_kernel, dim3(waves / bass::kWavesPerWorkgroup), dim3(64 * bass::kWavesPerWorkgroup), 0,
-                     (hipStream_t)stream, (const uint4*)K, (const uint4*)V, (int)nblocks, (int)waves, sink);
+  const int wpw = bass::waves_per_workgroup(waves);  // the workgroup shape of an attention launch of as many wavefronts
+  hipLaunchKernelGGL(bass::stream_read_kernel, dim3(waves / wpw), dim3(64 * wpw), 0, (hipStream_t)stream, (const uint4*)K,
+                     (const uint4*)V, (int)nblocks, (int)waves, sink);
   if (bass::launch_status() != BASS_OK) return BASS_ERR_HIP;
   return (int64_t)(nblocks * 2 * 8192);
 }

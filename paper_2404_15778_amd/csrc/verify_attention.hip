@@ -1594,7 +1594,7 @@ static int launch_attention(const bass_attn_desc* d, const LaunchShape& ls, cons
   p.part_ml = (float*)((char*)workspace + wl.part_ml);
 
   hipStream_t s = (hipStream_t)stream;
-  p.wpw = kWavesPerWorkgroup;
+  p.wpw = waves_per_workgroup(p.nwaves);
   const dim3 grid(p.nwaves / p.wpw), block(64 * p.wpw);
   if (d->dtype == BASS_DTYPE_FP32) {
     hipLaunchKernelGGL(verify_attn_fp32, grid, block, 0, s, p);

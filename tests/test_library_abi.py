@@ -121,3 +121,22 @@ def test_recorded_hbm_traffic_belongs_to_this_library_version():
     assert algorithmic == 158515200
     assert 1.0 <= traffic / algorithmic <= 1.15
     assert bench.measured_traffic(bass.bass_version() + 1) is None
+
+
+def test_one_hip_runtime_whatever_is_imported_first():
+    """torch's wheel ships its own HIP runtime; the process must end up with that one alone, also when the
+    binding is used before torch was imported (two runtimes: launches through one on memory of the other fail)."""
+    import subprocess
+    import sys
+    code = (
+        "import os, sys\n"
+        f"sys.path.insert(0, {ROOT!r})\n"
+        "import paper_2404_15778_amd as bass\n"
+        "assert bass.bass_version() >= 100\n"
+        "import torch\n"
+        "paths = {l.split()[-1] for l in open(f'/proc/{os.getpid()}/maps') if 'libamdhip64' in l}\n"
+        "print(len(paths), sorted(paths))\n"
+    )
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split()[0] == "1", out.stdout
