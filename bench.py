@@ -362,7 +362,7 @@ def main():
     kv_bytes = step.kv_bytes()
     value = kv_bytes * NL / (wall / args.steps) / 1e9
     n_acc_host = harness.to_host(step.n_accept)
-    waves_in_effect = args.waves if args.waves else ("library default (1024)" if args.kv_int8 else bass.bass_set_attention_waves(0))
+    waves_in_effect = args.waves if args.waves else bass.bass_set_attention_waves(0)
 
     def frac_of(kvb, us):
         return kvb / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS

@@ -318,12 +318,11 @@ int32_t bass_next_draft_len(bass_draft_len_state* state, const int32_t* n_accept
                             int32_t l_incre, int32_t l_mod, int32_t l_limit);
 
 /*
- * Tuning knob (host state, process wide): number of wavefronts the bf16/fp32 attention
- * kernel spreads the flattened (sequence, kv-head, context-block) work over.  Values are
- * clamped to [64, 8192]; 0 restores the defaults, which depend on the call: 768 for bf16 / fp32 with up
- * to 16 query rows per kv head, 1024 for INT8 caches, 256 workgroups of four wavefronts for bf16 caches
- * with more query rows (a setting W gives W / 2 workgroups there).  Returns the value in effect for
- * the first of these cases.  (A launch of 768 wavefronts runs as 256 workgroups of three, one per compute
+ * Tuning knob (host state, process wide): number of wavefronts the attention kernels spread the
+ * flattened (sequence, kv-head, context-block) work over.  Values are clamped to [64, 8192]; 0 restores
+ * the defaults, which depend on the call: 768 with up to 16 query rows per kv head; with more, 1024 for
+ * INT8 caches and 256 workgroups of four wavefronts for bf16 caches (a setting W gives W / 2 workgroups
+ * there).  Returns the value in effect for the first of these cases.  (A launch of 768 wavefronts runs as 256 workgroups of three, one per compute
  * unit; every other count as workgroups of four.)
  */
 int bass_set_attention_waves(int waves);

@@ -1,7 +1,7 @@
 // Version and status strings of libbass, and the host-side draft-length heuristic.
 #include "bass_common.h"
 
-extern "C" int bass_version(void) { return 211; /* 0.2.11: step plans (bass_attention_plan) drive every attention launch; bass_warp_accept; 768-wavefront launches as 256 workgroups of three */ }
+extern "C" int bass_version(void) { return 212; /* 0.2.12: step plans (bass_attention_plan) drive every attention launch; bass_warp_accept; 768-wavefront launches as 256 workgroups of three */ }
 
 extern "C" const char* bass_status_string(int code) {
   switch (code) {

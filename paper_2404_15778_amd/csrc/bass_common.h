@@ -140,11 +140,12 @@ struct LaunchShape {
 };
 
 // many_rows: more than one 16-row query tile per kv head (grouped-query attention); a separate
-// launch merges the partials there, and a slightly wider spread measured best (896)
-// int8: INT8 caches; the kernel is bound by the conversion instructions there, not by memory, and
-// uses every SIMD (1024)
+// launch merges the partials there, and a wider spread measured best: 896, and with INT8 caches, where the
+// kernel is bound by its conversion instructions, every SIMD (1024).  One query tile: 768 for INT8 caches
+// too -- as 256 workgroups of three they measured level with 1024 on the long-context shape and 2 - 3 %
+// shorter on the benchmark shape (a fourth wavefront on a compute unit costs the others issue slots).
 inline int attention_waves(int setting, bool many_rows, bool int8) {
-  int w = setting > 0 ? setting : (int8 ? 1024 : many_rows ? 896 : kDefaultWaves);
+  int w = setting > 0 ? setting : (many_rows ? (int8 ? 1024 : 896) : kDefaultWaves);
   if (w < 64) w = 64;
   if (w > kMaxWaves) w = kMaxWaves;
   return w - w % kWavesPerWorkgroup;

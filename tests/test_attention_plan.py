@@ -164,6 +164,9 @@ def test_paper_shaped_batches():
     check_plan(mk(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap), w.ctx_len, w.draft_len, 0, 0, expect_shares=256)
     check_plan(mk(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, "int8kv"), w.ctx_len, w.draft_len, bass.PLAN_APPEND, 0,
                expect_shares=1024)
+    w = wl.config2(0, tensors=False)  # INT8 caches with one query tile per kv head: the bf16 default
+    check_plan(mk(w.B, w.kmax, w.Hq, w.Hkv, w.D, w.Lcap, "int8kv"), w.ctx_len, w.draft_len, bass.PLAN_APPEND, 0,
+               expect_shares=768)
 
 
 @pytest.mark.parametrize("seed", range(40))
