@@ -140,3 +140,22 @@ def test_one_hip_runtime_whatever_is_imported_first():
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr
     assert out.stdout.split()[0] == "1", out.stdout
+
+
+def test_inline_assembly_is_limited_to_wait_counts():
+    """The compiler inserts the wait states some instruction pairs need (a vector-memory instruction behind a
+    vector instruction that wrote its scalar address, ...) only for instructions it emits itself, not for
+    opaque assembly text.  The kernels therefore contain no instruction written as inline assembly except
+    `s_waitcnt vmcnt(0)`, which has no operands; empty assembly strings (optimisation barriers) are fine."""
+    import glob
+    found = []
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2404_15778_amd", "csrc", "*"))):
+        text = open(path).read()
+        for m in re.finditer(r'\basm\s+volatile\s*\(\s*"((?:[^"\\]|\\.)*)"', text):
+            found.append((os.path.basename(path), m.group(1)))
+        # every asm statement is of the form matched above
+        assert len(re.findall(r'\basm\b', re.sub(r'//[^\n]*', '', text))) == len(
+            re.findall(r'\basm\s+volatile\s*\(\s*"', re.sub(r'//[^\n]*', '', text))), path
+    assert found, "the sources are expected to hold the explicit acknowledgement waits"
+    for name, body in found:
+        assert body in ("", "s_waitcnt vmcnt(0)"), (name, body)
