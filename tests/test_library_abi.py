@@ -159,3 +159,13 @@ def test_inline_assembly_is_limited_to_wait_counts():
     assert found, "the sources are expected to hold the explicit acknowledgement waits"
     for name, body in found:
         assert body in ("", "s_waitcnt vmcnt(0)"), (name, body)
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """The build runs on one GPU; asking the benchmark for more ends with a message, before any GPU is touched."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert out.returncode == 2
+    assert "ONE GPU" in out.stderr and out.stdout.strip() == ""
